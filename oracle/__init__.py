@@ -1,0 +1,178 @@
+"""ctypes wrapper around the CPU oracle (``mrp_oracle.c``).
+
+TEST INFRASTRUCTURE ONLY: imported by ``tests/``, ``__graft_entry__.smoke()``
+and ``bench.py``'s cpu_baseline leg; never by the product package.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from dataclasses import dataclass
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mrp_oracle.c")
+_LIB = os.path.join(_HERE, "libmrp_oracle.so")
+CFLAGS = ["-O2", "-fopenmp", "-std=c99", "-fPIC", "-shared", "-Wall"]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O2, OpenMP)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        subprocess.check_call(["gcc", *CFLAGS, _SRC, "-o", _LIB, "-lm"])
+    return _LIB
+
+
+class _Cfg(C.Structure):
+    _fields_ = [("d", C.c_int), ("V", C.c_int), ("B", C.c_int), ("L", C.c_int), ("K", C.c_int),
+                ("rms_eps", C.c_double), ("tau", C.c_double), ("r_min", C.c_int),
+                ("max_accept", C.c_int), ("carry_hidden", C.c_int), ("tau_remask", C.c_double),
+                ("head_reveal", C.c_int), ("fresh_block", C.c_int), ("state_offset", C.c_int)]
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_bf16_round.restype = C.c_double
+        _lib.orc_bf16_round.argtypes = [C.c_double]
+        _lib.orc_max_accept_cap.restype = C.c_int
+        _lib.orc_max_accept_cap.argtypes = [C.c_int, C.c_int]
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _chk(a, dtype, shape=None):
+    assert isinstance(a, np.ndarray) and a.dtype == dtype and a.flags["C_CONTIGUOUS"], (a.dtype, dtype)
+    if shape is not None:
+        assert tuple(a.shape) == tuple(shape), (a.shape, shape)
+    return a
+
+
+def make_cfg(d, V, B, L, K, tau=0.9, r_min=1, max_accept=0, carry_hidden=1, tau_remask=-1.0,
+             head_reveal=1, fresh_block=1, state_offset=0, rms_eps=1e-6) -> _Cfg:
+    return _Cfg(d, V, B, L, K, rms_eps, tau, r_min, max_accept, carry_hidden, tau_remask,
+                head_reveal, fresh_block, state_offset)
+
+
+def bf16_round(x: np.ndarray) -> np.ndarray:
+    x = np.ascontiguousarray(x, dtype=np.float64)
+    out = np.empty_like(x)
+    lib().orc_bf16_round_array(_p(x), _p(out), C.c_long(x.size))
+    return out
+
+
+def max_accept_cap(n_masked: int, L: int) -> int:
+    return lib().orc_max_accept_cap(n_masked, L)
+
+
+def reduce_rows(z: np.ndarray):
+    z = _chk(z, np.float64)
+    M, V = z.shape
+    tok = np.empty(M, np.int32); conf = np.empty(M, np.float64); lse = np.empty(M, np.float64)
+    lib().orc_reduce_rows(_p(z), M, V, _p(tok), _p(conf), _p(lse))
+    return tok, conf, lse
+
+
+def head_mlp(cfg: _Cfg, W1, W2, gamma, E, cond_tok, hrun):
+    """Returns (u, y); ``hrun`` [M][d] float64 is updated in place if carry_hidden."""
+    M, d = cfg.B * cfg.L, cfg.d
+    _chk(W1, np.uint16, (d, 2 * d)); _chk(W2, np.uint16, (d, d)); _chk(gamma, np.uint16, (d,))
+    _chk(E, np.uint16); _chk(cond_tok, np.int32, (cfg.B,)); _chk(hrun, np.float64, (M, d))
+    assert E.shape[1] == d and cond_tok.min() >= 0 and cond_tok.max() < E.shape[0]
+    u = np.empty((M, d)); y = np.empty((M, d))
+    lib().orc_head_mlp(C.byref(cfg), _p(W1), _p(W2), _p(gamma), _p(E), _p(cond_tok), _p(hrun), _p(u), _p(y))
+    return u, y
+
+
+def lm_head_add(W_lm, y, z):
+    V, d = W_lm.shape
+    M = y.shape[0]
+    _chk(W_lm, np.uint16); _chk(y, np.float64, (M, d)); _chk(z, np.float64, (M, V))
+    lib().orc_lm_head_add(_p(W_lm), _p(y), _p(z), M, V, d)
+
+
+def reveal(cfg: _Cfg, state, conf, tok, masked, revealed_at, cond_tok):
+    """In-place on masked / revealed_at / cond_tok; returns (draft_pos, draft_tok, top_pos)."""
+    M = cfg.B * cfg.L
+    _chk(conf, np.float64, (M,)); _chk(tok, np.int32, (M,)); _chk(masked, np.uint8, (M,))
+    _chk(revealed_at, np.int8, (M,)); _chk(cond_tok, np.int32, (cfg.B,))
+    dp = np.empty(cfg.B, np.int32); dt = np.empty(cfg.B, np.int32); tp = np.empty(cfg.B, np.int32)
+    lib().orc_reveal(C.byref(cfg), int(state), _p(conf), _p(tok), _p(masked), _p(revealed_at),
+                     _p(dp), _p(dt), _p(cond_tok), _p(tp))
+    return dp, dt, tp
+
+
+def remask(B, L, state, conf, tau_remask, protect_pos, masked, revealed_at):
+    M = B * L
+    _chk(conf, np.float64, (M,)); _chk(masked, np.uint8, (M,)); _chk(revealed_at, np.int8, (M,))
+    if protect_pos is not None:
+        _chk(protect_pos, np.int32, (B,))
+    out = np.empty(M, np.uint8)
+    lib().orc_remask(B, L, int(state), _p(conf), C.c_double(tau_remask), _p(protect_pos), _p(masked),
+                     _p(revealed_at), _p(out))
+    return out
+
+
+def verify_accept(verify, draft_pos, draft_tok):
+    B, L, V = verify.shape
+    K = draft_pos.shape[1]
+    _chk(verify, np.float32); _chk(draft_pos, np.int32, (B, K)); _chk(draft_tok, np.int32, (B, K))
+    match = np.empty((B, K), np.uint8); alen = np.empty(B, np.int32); corr = np.empty(B, np.int32)
+    lib().orc_verify_accept(B, L, V, K, _p(verify), _p(draft_pos), _p(draft_tok), _p(match), _p(alen), _p(corr))
+    return match, alen, corr
+
+
+@dataclass
+class ChainOut:
+    z: np.ndarray            # [M][V] float64, final logit state
+    hrun: np.ndarray         # [M][d] float64
+    tok: np.ndarray          # [(K+1)][M]
+    conf: np.ndarray
+    lse: np.ndarray
+    masked: np.ndarray
+    revealed_at: np.ndarray
+    cond_tok: np.ndarray
+    protect_pos: np.ndarray
+    draft_pos: np.ndarray    # [B][K+1]
+    draft_tok: np.ndarray
+    remasked: np.ndarray     # [(K+1)][M]
+    y: Optional[np.ndarray]  # [K][M][d] bf16-rounded LM-head operand
+
+
+def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, revealed_at=None,
+               cond_tok=None, protect_pos=None, dump_y=False) -> ChainOut:
+    """One chain step.  ``z`` [M][V] and ``hrun`` [M][d] float64 are copied, not modified."""
+    M, d, V, K, B = cfg.B * cfg.L, cfg.d, cfg.V, cfg.K, cfg.B
+    assert len(heads) == K
+    _chk(E, np.uint16); _chk(W_lm, np.uint16, (V, d))
+    assert E.shape[1] == d
+    z = np.array(_chk(np.ascontiguousarray(z, dtype=np.float64), np.float64, (M, V)))
+    hrun = np.array(_chk(np.ascontiguousarray(hrun, dtype=np.float64), np.float64, (M, d)))
+    for (w1, w2, g) in heads:
+        _chk(w1, np.uint16, (d, 2 * d)); _chk(w2, np.uint16, (d, d)); _chk(g, np.uint16, (d,))
+    PT = C.c_void_p * max(K, 1)
+    w1s = PT(*[h[0].ctypes.data for h in heads]); w2s = PT(*[h[1].ctypes.data for h in heads])
+    gs = PT(*[h[2].ctypes.data for h in heads])
+    tok = np.full((K + 1, M), -1, np.int32); conf = np.zeros((K + 1, M)); lse = np.zeros((K + 1, M))
+    masked = np.ones(M, np.uint8) if masked is None else np.array(masked, np.uint8)
+    revealed_at = np.full(M, -1, np.int8) if revealed_at is None else np.array(revealed_at, np.int8)
+    cond_tok = np.zeros(B, np.int32) if cond_tok is None else np.array(cond_tok, np.int32)
+    protect_pos = np.full(B, -1, np.int32) if protect_pos is None else np.array(protect_pos, np.int32)
+    assert cond_tok.min() >= 0 and cond_tok.max() < E.shape[0]
+    dpos = np.empty((B, K + 1), np.int32); dtok = np.empty((B, K + 1), np.int32)
+    rem = np.zeros((K + 1, M), np.uint8)
+    y = np.empty((K, M, d)) if dump_y else None
+    lib().orc_chain_step(C.byref(cfg), _p(E), _p(W_lm), w1s, w2s, gs, _p(z), _p(hrun), _p(tok), _p(conf),
+                         _p(lse), _p(masked), _p(revealed_at), _p(cond_tok), _p(protect_pos), _p(dpos),
+                         _p(dtok), _p(rem), _p(y))
+    return ChainOut(z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos, dpos, dtok, rem, y)

@@ -1,0 +1,312 @@
+/*
+ * CPU oracle for the MRP chain step.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, fp64 statement of what one denoising step's chain of K
+ * Multi-token Residual Prediction heads computes.  It exists so that the GPU
+ * library can be checked against something that is obviously right; only the
+ * tests, the smoke check and the benchmark's cpu_baseline leg may call it.
+ * It shares no code, header, table or helper with the GPU path.
+ *
+ * What follows the paper and where:
+ *   - confidence = top-1 softmax probability of a row of logits
+ *       (Section 2, "Denoising Loop").
+ *   - one MRP step: (Delta, delta) <- g(x, h); h <- h + Delta;
+ *       l <- l + delta; then reveal / draft from softmax(l)
+ *       (Section 3.4, Algorithm 2 inner loop; Algorithm 3 drafting loop).
+ *   - the head reuses the backbone's LM head to turn its output into the
+ *       residual logits (Section 3.2).
+ *   - dynamic reveal: every masked position whose confidence exceeds tau,
+ *       at least one per step (Section 4.1 "Denoising Mode"); static reveal
+ *       of the r most confident is the same rule with tau >= 1, r_min = r.
+ *   - max-accept cap m = min(max(floor(0.7 n), 5), L) (Section 4.4).
+ *   - remask: positions revealed earlier in this step whose updated
+ *       confidence is below the remask threshold (Section 3.4, Algorithm 4).
+ *   - verify: a draft is accepted where the verifier's argmax equals the
+ *       drafted token (Algorithm 3); the accepted length is the longest
+ *       all-matching prefix of the draft list.
+ *
+ * The head body is the benchmark's lightweight layout (not the paper's
+ * transformer layers): x = [h ; E[cond_tok]], a = W1 x, s = SiLU(a),
+ * u = W2 s, Delta = u, y = bf16(RMSNorm(u) * gamma), delta = W_lm y.
+ * The only rounding of an intermediate is y -> bf16: the LM-head projection
+ * is defined on a bf16 activation operand.  Everything else is fp64.
+ *
+ * Ties: lowest vocabulary index wins an argmax; lowest position wins a
+ * confidence tie.  Reveal compares strictly (conf > tau), remask compares
+ * strictly (conf < tau_remask).
+ *
+ * Pins (tests -m "not gpu"): library logsumexp / matmul on random shapes,
+ * closed forms (uniform row, one-hot-plus-a row), shift invariance,
+ * permutation equivariance, sum of probabilities, zero-residual invariance,
+ * the softmax half-Lipschitz bound, tau = 0 / tau >= 1 reveal sets, the cap
+ * values, brute-force longest matching prefix, remask set inclusions.
+ * Parity unpinned: the end-to-end numeric values of the head layout (the
+ * paper prints no worked example); they are pinned only through the library
+ * matmul composition and the invariants above.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+typedef struct {
+    int d, V, B, L, K;
+    double rms_eps;
+    double tau;          /* reveal threshold, strict >                       */
+    int r_min;           /* forced minimum number of reveals per state       */
+    int max_accept;      /* 1: cap the number of threshold reveals           */
+    int carry_hidden;    /* 1: h <- h + Delta between heads                  */
+    double tau_remask;   /* < 0: no remask                                    */
+    int head_reveal;     /* 1: reveal after every head (Alg. 2/3); 0: Alg. 4 */
+    int fresh_block;     /* 1: state 0 starts from an all-masked block       */
+    int state_offset;    /* 0: run state 0; s > 0: resume after state s      */
+} orc_cfg;
+
+static double bf16_bits_to_double(uint16_t b) {
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return (double)f;
+}
+
+/* Nearest bf16 value (8 significant bits, ties to even), as a double.
+ * Normal range only: |x| far from the fp32 exponent limits. */
+double orc_bf16_round(double x) {
+    if (x == 0.0 || !isfinite(x)) return x;
+    int e;
+    double m = frexp(x, &e);            /* |m| in [0.5, 1) */
+    double q = nearbyint(m * 256.0);    /* default mode: ties to even */
+    return ldexp(q / 256.0, e);
+}
+
+void orc_bf16_round_array(const double *x, double *out, long n) {
+    for (long i = 0; i < n; ++i) out[i] = orc_bf16_round(x[i]);
+}
+
+/* Per row: m = max, s = sum exp(z - m), tok = lowest index attaining m,
+ * conf = 1/s (top-1 probability), lse = m + log s. */
+void orc_reduce_rows(const double *z, int M, int V, int32_t *tok, double *conf, double *lse) {
+#pragma omp parallel for schedule(static)
+    for (int i = 0; i < M; ++i) {
+        const double *r = z + (size_t)i * V;
+        double m = r[0];
+        int am = 0;
+        for (int v = 1; v < V; ++v)
+            if (r[v] > m) { m = r[v]; am = v; }
+        double s = 0.0;
+        for (int v = 0; v < V; ++v) s += exp(r[v] - m);
+        tok[i] = am;
+        conf[i] = 1.0 / s;
+        lse[i] = m + log(s);
+    }
+}
+
+/* Head body for every row i of every sequence b = i / L.
+ *   hrun [M][d] in/out (updated only if carry_hidden)
+ *   u_out, y_out [M][d] (may be NULL): pre-norm output and bf16-rounded
+ *   normalised output. */
+void orc_head_mlp(const orc_cfg *c, const uint16_t *W1, const uint16_t *W2, const uint16_t *gamma,
+                  const uint16_t *E, const int32_t *cond_tok, double *hrun, double *u_out,
+                  double *y_out) {
+    const int d = c->d, M = c->B * c->L;
+#pragma omp parallel
+    {
+        double *x = (double *)malloc(sizeof(double) * 2 * d);
+        double *s = (double *)malloc(sizeof(double) * d);
+        double *u = (double *)malloc(sizeof(double) * d);
+#pragma omp for schedule(static)
+        for (int i = 0; i < M; ++i) {
+            const int b = i / c->L;
+            const uint16_t *e = E + (size_t)cond_tok[b] * d;
+            for (int j = 0; j < d; ++j) x[j] = hrun[(size_t)i * d + j];
+            for (int j = 0; j < d; ++j) x[d + j] = bf16_bits_to_double(e[j]);
+            for (int j = 0; j < d; ++j) {
+                const uint16_t *w = W1 + (size_t)j * 2 * d;
+                double a = 0.0;
+                for (int k = 0; k < 2 * d; ++k) a += bf16_bits_to_double(w[k]) * x[k];
+                s[j] = a * (1.0 / (1.0 + exp(-a)));          /* SiLU */
+            }
+            double ss = 0.0;
+            for (int j = 0; j < d; ++j) {
+                const uint16_t *w = W2 + (size_t)j * d;
+                double acc = 0.0;
+                for (int k = 0; k < d; ++k) acc += bf16_bits_to_double(w[k]) * s[k];
+                u[j] = acc;
+                ss += acc * acc;
+            }
+            const double inv = 1.0 / sqrt(ss / d + c->rms_eps);
+            for (int j = 0; j < d; ++j) {
+                const double y = orc_bf16_round(u[j] * inv * bf16_bits_to_double(gamma[j]));
+                if (y_out) y_out[(size_t)i * d + j] = y;
+                if (u_out) u_out[(size_t)i * d + j] = u[j];
+                if (c->carry_hidden) hrun[(size_t)i * d + j] += u[j];
+            }
+        }
+        free(x); free(s); free(u);
+    }
+}
+
+/* z[i][v] += sum_c W_lm[v][c] * y[i][c]   (shared LM head, residual add) */
+void orc_lm_head_add(const uint16_t *W_lm, const double *y, double *z, int M, int V, int d) {
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int i = 0; i < M; ++i) {
+        for (int v = 0; v < V; ++v) {
+            const uint16_t *w = W_lm + (size_t)v * d;
+            const double *yi = y + (size_t)i * d;
+            double acc = 0.0;
+            for (int k = 0; k < d; ++k) acc += bf16_bits_to_double(w[k]) * yi[k];
+            z[(size_t)i * V + v] += acc;
+        }
+    }
+}
+
+/* a before b in "most confident" order: higher confidence, then lower position */
+static int more_confident(const double *conf, int a, int b) {
+    if (conf[a] != conf[b]) return conf[a] > conf[b];
+    return a < b;
+}
+
+int orc_max_accept_cap(int n_masked, int L) {
+    int m = (7 * n_masked) / 10;       /* floor(0.7 n) in integers */
+    if (m < 5) m = 5;
+    if (m > L) m = L;
+    return m;
+}
+
+/* Reveal rule for one state, all sequences.  conf/tok are this state's. */
+void orc_reveal(const orc_cfg *c, int state, const double *conf, const int32_t *tok,
+                uint8_t *masked, int8_t *revealed_at, int32_t *draft_pos, int32_t *draft_tok,
+                int32_t *cond_tok, int32_t *top_pos /* [B] or NULL */) {
+    const int L = c->L;
+    int *sel = (int *)malloc(sizeof(int) * L);
+    int *cand = (int *)malloc(sizeof(int) * L);
+    for (int b = 0; b < c->B; ++b) {
+        const double *cf = conf + (size_t)b * L;
+        uint8_t *mk = masked + (size_t)b * L;
+        int nc = 0;
+        for (int p = 0; p < L; ++p) if (mk[p]) cand[nc++] = p;
+        draft_pos[b] = -1; draft_tok[b] = -1;
+        if (top_pos) top_pos[b] = -1;
+        if (nc == 0) continue;
+        /* candidates in most-confident-first order (insertion sort) */
+        for (int a = 1; a < nc; ++a) {
+            int p = cand[a], q = a - 1;
+            while (q >= 0 && more_confident(cf, p, cand[q])) { cand[q + 1] = cand[q]; --q; }
+            cand[q + 1] = p;
+        }
+        int ns = 0;
+        for (int a = 0; a < nc; ++a) if (cf[cand[a]] > c->tau) sel[ns++] = cand[a];
+        if (c->max_accept) {
+            int m = orc_max_accept_cap(nc, L);
+            if (ns > m) ns = m;        /* sel is already most-confident-first */
+        }
+        if (ns < c->r_min) {
+            ns = c->r_min < nc ? c->r_min : nc;
+            for (int a = 0; a < ns; ++a) sel[a] = cand[a];
+        }
+        if (ns == 0) continue;
+        for (int a = 0; a < ns; ++a) {
+            mk[sel[a]] = 0;
+            revealed_at[(size_t)b * L + sel[a]] = (int8_t)state;
+        }
+        const int top = sel[0];
+        draft_pos[b] = top;
+        draft_tok[b] = tok[(size_t)b * L + top];
+        cond_tok[b] = tok[(size_t)b * L + top];
+        if (top_pos) top_pos[b] = top;
+    }
+    free(sel); free(cand);
+}
+
+/* Remask rule for one state: rows revealed at a state in [0, state-1] of this
+ * chain step, not the protected position, whose confidence is < tau_remask. */
+void orc_remask(int B, int L, int state, const double *conf, double tau_remask,
+                const int32_t *protect_pos, uint8_t *masked, int8_t *revealed_at,
+                uint8_t *remasked) {
+    for (int b = 0; b < B; ++b)
+        for (int p = 0; p < L; ++p) {
+            const size_t i = (size_t)b * L + p;
+            remasked[i] = 0;
+            const int ra = revealed_at[i];
+            if (ra < 0 || ra > state - 1) continue;
+            if (protect_pos && protect_pos[b] == p) continue;
+            if (conf[i] < tau_remask) { masked[i] = 1; revealed_at[i] = -1; remasked[i] = 1; }
+        }
+}
+
+/* Verify K drafts per sequence against verifier logits [B][L][V]. */
+void orc_verify_accept(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
+                       const int32_t *draft_tok, uint8_t *match, int32_t *accept_len,
+                       int32_t *correction_tok) {
+    for (int b = 0; b < B; ++b) {
+        int alen = 0, open = 1;
+        correction_tok[b] = -1;
+        for (int j = 0; j < K; ++j) {
+            const int pos = draft_pos[(size_t)b * K + j];
+            int vj = -1, ok = 0;
+            if (pos >= 0) {
+                const float *r = verify + ((size_t)b * L + pos) * V;
+                float m = r[0];
+                vj = 0;
+                for (int v = 1; v < V; ++v) if (r[v] > m) { m = r[v]; vj = v; }
+                ok = (vj == draft_tok[(size_t)b * K + j]);
+            }
+            match[(size_t)b * K + j] = (uint8_t)ok;
+            if (open) {
+                if (ok) ++alen;
+                else { open = 0; correction_tok[b] = vj; }
+            }
+        }
+        accept_len[b] = alen;
+    }
+}
+
+/* One denoising step's chain.
+ *   z       [M][V] fp64 in/out         hrun [M][d] fp64 in/out
+ *   heads   K triples of bf16 arrays   (W1[k], W2[k], gamma[k])
+ *   tok/conf/lse [(K+1)][M]; slot 0 = state 0 (untouched when resuming)
+ *   masked, revealed_at [M] in/out; cond_tok, protect_pos [B] in/out
+ *   draft_pos/draft_tok [B][K+1] (column = local state index)
+ *   remasked [(K+1)][M] (may be NULL)
+ *   y_dump  [K][M][d] (may be NULL) */
+void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
+                    const uint16_t *const *W1, const uint16_t *const *W2,
+                    const uint16_t *const *gamma, double *z, double *hrun, int32_t *tok,
+                    double *conf, double *lse, uint8_t *masked, int8_t *revealed_at,
+                    int32_t *cond_tok, int32_t *protect_pos, int32_t *draft_pos,
+                    int32_t *draft_tok, uint8_t *remasked, double *y_dump) {
+    const int M = c->B * c->L, K = c->K, B = c->B;
+    int32_t *dp = (int32_t *)malloc(sizeof(int32_t) * B);
+    int32_t *dt = (int32_t *)malloc(sizeof(int32_t) * B);
+    double *y = (double *)malloc(sizeof(double) * (size_t)M * c->d);
+    for (int b = 0; b < B; ++b)
+        for (int k = 0; k <= K; ++k) { draft_pos[b * (K + 1) + k] = -1; draft_tok[b * (K + 1) + k] = -1; }
+    if (remasked) memset(remasked, 0, (size_t)(K + 1) * M);
+
+    if (c->state_offset == 0) {
+        if (c->fresh_block)
+            for (int i = 0; i < M; ++i) { masked[i] = 1; revealed_at[i] = -1; }
+        orc_reduce_rows(z, M, c->V, tok, conf, lse);
+        orc_reveal(c, 0, conf, tok, masked, revealed_at, dp, dt, cond_tok, protect_pos);
+        for (int b = 0; b < B; ++b) { draft_pos[b * (K + 1)] = dp[b]; draft_tok[b * (K + 1)] = dt[b]; }
+    }
+    for (int k = 1; k <= K; ++k) {
+        const int state = c->state_offset + k;
+        orc_head_mlp(c, W1[k - 1], W2[k - 1], gamma[k - 1], E, cond_tok, hrun, NULL, y);
+        if (y_dump) memcpy(y_dump + (size_t)(k - 1) * M * c->d, y, sizeof(double) * (size_t)M * c->d);
+        orc_lm_head_add(W_lm, y, z, M, c->V, c->d);
+        orc_reduce_rows(z, M, c->V, tok + (size_t)k * M, conf + (size_t)k * M, lse + (size_t)k * M);
+        if (c->head_reveal) {
+            orc_reveal(c, state, conf + (size_t)k * M, tok + (size_t)k * M, masked, revealed_at,
+                       dp, dt, cond_tok, NULL);
+            for (int b = 0; b < B; ++b) { draft_pos[b * (K + 1) + k] = dp[b]; draft_tok[b * (K + 1) + k] = dt[b]; }
+        }
+        if (c->tau_remask >= 0.0) {
+            uint8_t *rm = remasked ? remasked + (size_t)k * M : (uint8_t *)malloc(M);
+            orc_remask(B, c->L, state, conf + (size_t)k * M, c->tau_remask, protect_pos, masked,
+                       revealed_at, rm);
+            if (!remasked) free(rm);
+        }
+    }
+    free(dp); free(dt); free(y);
+}

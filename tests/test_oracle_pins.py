@@ -1,0 +1,426 @@
+"""Pins for the CPU oracle: each piece is checked against something other than
+itself — a library routine, a closed form, an invariant the paper or the
+mathematics fixes, or brute force on tiny inputs."""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+from scipy.special import logsumexp
+
+import mrp_inputs as mi
+import oracle as orc
+
+RNG = np.random.default_rng(12345)
+HERE = os.path.dirname(os.path.abspath(__file__))
+
+
+def bits(x):
+    return mi.f32_to_bf16_bits(np.asarray(x, np.float32))
+
+
+def val(b):
+    return mi.bf16_bits_to_f64(b)
+
+
+# ------------------------------------------------------------------ reduction
+def test_reduce_matches_library_logsumexp():
+    for V in (1, 2, 7, 1000, 4099):
+        z = RNG.normal(0, 2, (5, V))
+        tok, conf, lse = orc.reduce_rows(z)
+        np.testing.assert_allclose(lse, logsumexp(z, axis=1), rtol=1e-13, atol=1e-13)
+        np.testing.assert_array_equal(tok, z.argmax(1))
+        np.testing.assert_allclose(conf, np.exp(z.max(1) - logsumexp(z, axis=1)), rtol=1e-12)
+
+
+def test_reduce_closed_forms():
+    V = 4096
+    # uniform row: conf = 1/V, lowest index wins the tie
+    tok, conf, lse = orc.reduce_rows(np.full((1, V), 3.25))
+    assert tok[0] == 0 and abs(conf[0] - 1.0 / V) < 1e-15 and abs(lse[0] - (3.25 + np.log(V))) < 1e-12
+    # one-hot plus a: conf = e^a / (e^a + V - 1)
+    for a, at in ((2.0, 17), (12.0, V - 1), (0.5, 0)):
+        z = np.zeros((1, V)); z[0, at] = a
+        tok, conf, _ = orc.reduce_rows(z)
+        assert tok[0] == at
+        assert abs(conf[0] - np.exp(a) / (np.exp(a) + V - 1)) < 1e-14
+    # exact tie between two maxima: lowest index
+    z = RNG.normal(0, 1, (1, 50)); z[0, 40] = 9.0; z[0, 11] = 9.0
+    assert orc.reduce_rows(z)[0][0] == 11
+
+
+def test_reduce_shift_invariance_and_permutation_equivariance():
+    z = RNG.normal(0, 2, (4, 513))
+    tok, conf, lse = orc.reduce_rows(z)
+    tok2, conf2, lse2 = orc.reduce_rows(z + 7.5)          # normalising constants cancel
+    np.testing.assert_array_equal(tok, tok2)
+    np.testing.assert_allclose(conf, conf2, rtol=1e-12)
+    np.testing.assert_allclose(lse2 - lse, 7.5, rtol=1e-12)
+    perm = RNG.permutation(513)
+    tok3, conf3, lse3 = orc.reduce_rows(np.ascontiguousarray(z[:, perm]))
+    np.testing.assert_array_equal(perm[tok3], tok)
+    np.testing.assert_allclose(conf3, conf, rtol=1e-12)
+    np.testing.assert_allclose(lse3, lse, rtol=1e-12)
+
+
+def test_probabilities_sum_to_one():
+    z = RNG.normal(0, 2, (6, 4096)); z[2, 5] += 12
+    _, conf, lse = orc.reduce_rows(z)
+    p = np.exp(z - lse[:, None])
+    np.testing.assert_allclose(p.sum(1), 1.0, atol=1e-12)
+    np.testing.assert_allclose(p.max(1), conf, rtol=1e-12)
+
+
+# ------------------------------------------------------------------ bf16 cast
+def test_bf16_round_matches_library_cast():
+    x = np.concatenate([RNG.normal(0, 1, 20000), RNG.normal(0, 1e-3, 2000), RNG.normal(0, 300, 2000),
+                        # exact ties between neighbouring bf16 values, both parities
+                        np.array([1.0 + 2 ** -8, 1.0 + 3 * 2 ** -8, -(2.0 + 2 ** -7), 0.0, 1.0, -0.5])])
+    x = x.astype(np.float32).astype(np.float64)            # fp32-representable inputs
+    ref = torch.from_numpy(x.astype(np.float32)).to(torch.bfloat16).to(torch.float64).numpy()
+    np.testing.assert_array_equal(orc.bf16_round(x), ref)
+    # and the generator's own bit-level rounding agrees with the library cast as well
+    np.testing.assert_array_equal(val(bits(x)), ref)
+
+
+# ------------------------------------------------------------------ head body
+def _rand_head(d, V, scale=0.2):
+    W1 = bits(RNG.normal(0, scale, (d, 2 * d))); W2 = bits(RNG.normal(0, scale, (d, d)))
+    g = bits(RNG.normal(1, 0.3, d)); E = bits(RNG.normal(0, 1, (V, d)))
+    return W1, W2, g, E
+
+
+def _numpy_head(W1, W2, g, E, cond_tok, hrun, L, eps=1e-6):
+    """Library-matmul statement of the head body (independent of the C code)."""
+    M = hrun.shape[0]
+    e = val(E)[np.repeat(cond_tok, L)]
+    x = np.concatenate([hrun, e], axis=1)                   # h first, then the embedding
+    a = x @ val(W1).T
+    s = a / (1.0 + np.exp(-a))
+    u = s @ val(W2).T
+    y = u / np.sqrt((u * u).mean(1, keepdims=True) + eps) * val(g)[None, :]
+    return u, y
+
+
+@pytest.mark.parametrize("d,V,B,L", [(8, 16, 2, 3), (64, 100, 3, 4), (256, 4096, 1, 4)])
+def test_head_mlp_matches_library_matmul(d, V, B, L):
+    W1, W2, g, E = _rand_head(d, V)
+    cfg = orc.make_cfg(d, V, B, L, 1)
+    hrun = RNG.normal(0, 1, (B * L, d))
+    cond = RNG.integers(0, V, B).astype(np.int32)
+    h0 = hrun.copy()
+    u, y = orc.head_mlp(cfg, W1, W2, g, E, cond, hrun)
+    u_ref, y_ref = _numpy_head(W1, W2, g, E, cond, h0, L)
+    np.testing.assert_allclose(u, u_ref, rtol=1e-11, atol=1e-12)
+    # y is the bf16 rounding of the normalised output: within half a bf16 step of it,
+    # and exactly representable in bf16
+    assert np.all(np.abs(y - y_ref) <= np.abs(y_ref) * 2.0 ** -8 + 1e-30)
+    np.testing.assert_array_equal(y, val(bits(y)))
+    np.testing.assert_allclose(hrun, h0 + u_ref, rtol=1e-11, atol=1e-12)      # h <- h + Delta
+    cfg2 = orc.make_cfg(d, V, B, L, 1, carry_hidden=0)
+    h1 = h0.copy()
+    orc.head_mlp(cfg2, W1, W2, g, E, cond, h1)
+    np.testing.assert_array_equal(h1, h0)
+
+
+def test_silu_and_rmsnorm_closed_forms():
+    d, V = 16, 4
+    eye = np.eye(d)
+    W1 = bits(np.concatenate([eye, np.zeros((d, d))], 1)); W2 = bits(eye)
+    g = bits(np.ones(d)); E = bits(np.zeros((V, d)))
+    cfg = orc.make_cfg(d, V, 1, 2, 1, carry_hidden=0)
+    a = RNG.normal(0, 3, d)
+    hrun = np.stack([a, -a]); hrun[:, 0] = 0.0
+    u, y = orc.head_mlp(cfg, W1, W2, g, E, np.zeros(1, np.int32), hrun)
+    assert u[0, 0] == 0.0                                                    # SiLU(0) = 0
+    np.testing.assert_allclose(u[0] - u[1], hrun[0], rtol=1e-13, atol=1e-15)   # SiLU(a) - SiLU(-a) = a
+    big = np.full((2, d), 40.0)
+    u2, _ = orc.head_mlp(cfg, W1, W2, g, E, np.zeros(1, np.int32), big)
+    np.testing.assert_allclose(u2, 40.0, rtol=1e-15)                            # SiLU(a) -> a
+    # RMSNorm with unit gain: unit RMS up to eps and the bf16 step
+    rms = np.sqrt((y * y).mean(1))
+    np.testing.assert_allclose(rms, 1.0, atol=4e-3)
+    # gain is applied elementwise after normalisation
+    g2 = bits(np.linspace(0.5, 2.0, d))
+    _, y2 = orc.head_mlp(cfg, W1, W2, g2, E, np.zeros(1, np.int32), hrun)
+    np.testing.assert_allclose(y2, y * val(g2)[None, :], rtol=2.0 ** -7, atol=1e-30)
+
+
+def test_embedding_row_and_concat_order():
+    """The embedding half of W1 sees E[cond_tok] of the row's own sequence."""
+    d, V, B, L = 8, 5, 2, 2
+    W1 = bits(np.concatenate([np.zeros((d, d)), np.eye(d)], 1)); W2 = bits(np.eye(d))
+    E = bits(RNG.normal(0, 2, (V, d))); g = bits(np.ones(d))
+    cfg = orc.make_cfg(d, V, B, L, 1, carry_hidden=0)
+    cond = np.array([3, 1], np.int32)
+    u, _ = orc.head_mlp(cfg, W1, W2, g, E, cond, RNG.normal(0, 1, (B * L, d)))
+    e = val(E)
+    for i in range(B * L):
+        ei = e[cond[i // L]]
+        np.testing.assert_allclose(u[i], ei / (1 + np.exp(-ei)), rtol=1e-13, atol=1e-15)
+
+
+def test_lm_head_add_matches_library_matmul():
+    for (M, V, d) in ((3, 17, 8), (5, 300, 64)):
+        W = bits(RNG.normal(0, 0.05, (V, d)))
+        y = val(bits(RNG.normal(0, 1, (M, d))))
+        z = RNG.normal(0, 2, (M, V)); z0 = z.copy()
+        orc.lm_head_add(W, y, z)
+        np.testing.assert_allclose(z, z0 + y @ val(W).T, rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------ chain
+def _tiny_problem(cid=0, **ov):
+    cfg = mi.config(cid, **ov)
+    return cfg, mi.lm_head(cfg), mi.embedding(cfg), [mi.head_weights(cfg, k) for k in range(cfg.K)], \
+        mi.hidden(cfg), mi.logits0(cfg)
+
+
+def test_zero_residual_leaves_logits_unchanged():
+    cfg, W, E, heads, h, z0 = _tiny_problem()
+    for variant in ("gamma", "w2"):
+        hs = []
+        for (w1, w2, g) in heads:
+            hs.append((w1, w2, np.zeros_like(g)) if variant == "gamma" else (w1, np.zeros_like(w2), g))
+        oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, tau=cfg.tau)
+        out = orc.chain_step(oc, E, W, hs, z0, val(h))
+        np.testing.assert_array_equal(out.z, z0.astype(np.float64))        # bit for bit
+        for k in range(1, cfg.K + 1):
+            np.testing.assert_array_equal(out.tok[k], out.tok[0])
+            np.testing.assert_array_equal(out.conf[k], out.conf[0])
+
+
+def test_chain_matches_library_composition_config0():
+    """Whole chain on the tiny configuration against a numpy restatement built from
+    library matmul / logsumexp (control flow: greedy forced reveal only)."""
+    cfg, W, E, heads, h, z0 = _tiny_problem()
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, tau=cfg.tau)
+    out = orc.chain_step(oc, E, W, heads, z0, val(h), dump_y=True)
+    z = z0.astype(np.float64); hrun = val(h)
+    masked = np.ones(cfg.M, bool)
+    for k in range(cfg.K + 1):
+        if k > 0:
+            u, y = _numpy_head(*heads[k - 1], E, cond, hrun, cfg.L)
+            hrun = hrun + u
+            yq = val(bits(y))
+            # identical rounding wherever y is not within 1e-9 (relative) of a rounding tie
+            step = 2.0 ** (np.floor(np.log2(np.abs(y) + 1e-300)) - 7)
+            frac = np.abs(y) / step % 1.0
+            safe = np.abs(frac - 0.5) > 1e-6
+            np.testing.assert_array_equal(out.y[k - 1][safe], yq[safe])
+            z = z + out.y[k - 1] @ val(W).T
+        lse = logsumexp(z, axis=1)
+        conf = np.exp(z.max(1) - lse)
+        np.testing.assert_array_equal(out.tok[k], z.argmax(1))
+        np.testing.assert_allclose(out.conf[k], conf, rtol=1e-9)
+        np.testing.assert_allclose(out.lse[k], lse, rtol=1e-11)
+        cond = np.empty(cfg.B, np.int32)
+        for b in range(cfg.B):
+            rows = np.arange(b * cfg.L, (b + 1) * cfg.L)
+            cand = rows[masked[rows]]
+            sel = cand[conf[cand] > cfg.tau]
+            if len(sel) == 0:
+                sel = cand[[np.argmax(conf[cand])]]
+            masked[sel] = False
+            top = sel[np.argmax(conf[sel])]
+            cond[b] = z[top].argmax()
+            assert out.draft_pos[b, k] == top - b * cfg.L and out.draft_tok[b, k] == cond[b]
+    np.testing.assert_allclose(out.z, z, rtol=1e-11, atol=1e-11)
+    np.testing.assert_array_equal(out.masked.astype(bool), masked)
+
+
+def test_tv_bound_half_lipschitz_softmax():
+    """TV(softmax(l + delta), softmax(l)) <= 0.5 * ||delta||_2 per row
+    (appendix proof of the one-step contraction proposition)."""
+    cfg, W, E, heads, h, z0 = _tiny_problem()
+    # scale gamma down so that the bound is not vacuous
+    hs = [(w1, w2, bits(np.full(cfg.d, 0.02))) for (w1, w2, _) in heads]
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, tau=cfg.tau)
+    out = orc.chain_step(oc, E, W, hs[:1], z0, val(h))
+    z_old = z0.astype(np.float64)
+    delta = out.z - z_old
+    p_old = np.exp(z_old - logsumexp(z_old, axis=1)[:, None])
+    p_new = np.exp(out.z - out.lse[1][:, None])
+    tv = 0.5 * np.abs(p_new - p_old).sum(1)
+    bound = 0.5 * np.sqrt((delta * delta).sum(1))
+    assert np.all(bound > 0) and np.all(bound < 1.0)
+    assert np.all(tv <= bound + 1e-15)
+
+
+# ------------------------------------------------------------------ reveal
+def _reveal_once(conf, tau, L, r_min=1, max_accept=0, masked=None):
+    M = len(conf); B = M // L
+    cfg = orc.make_cfg(4, 8, B, L, 1, tau=tau, r_min=r_min, max_accept=max_accept)
+    masked = np.ones(M, np.uint8) if masked is None else masked.copy()
+    ra = np.full(M, -1, np.int8)
+    tok = (np.arange(M) % 8).astype(np.int32)
+    cond = np.full(B, 7, np.int32)
+    dp, dt, tp = orc.reveal(cfg, 0, np.asarray(conf, np.float64), tok, masked, ra, cond)
+    return masked, ra, dp, dt, cond, tok
+
+
+def test_reveal_threshold_extremes():
+    L = 8
+    conf = RNG.uniform(0.01, 0.99, 3 * L)
+    masked, ra, dp, dt, cond, tok = _reveal_once(conf, 0.0, L)
+    assert masked.sum() == 0 and np.all(ra == 0)                      # tau = 0 reveals everything
+    for tau in (1.0, 1.5):                                           # forced token only
+        masked, ra, dp, dt, cond, tok = _reveal_once(conf, tau, L)
+        for b in range(3):
+            blk = slice(b * L, (b + 1) * L)
+            assert (masked[blk] == 0).sum() == 1
+            top = int(np.argmax(conf[blk]))
+            assert masked[blk][top] == 0 and dp[b] == top and dt[b] == tok[b * L + top] == cond[b]
+    # confidence exactly 1.0 does not exceed tau = 1.0 (direct decoding = forced reveals only)
+    c = conf.copy(); c[3] = 1.0; c[5] = 1.0
+    masked, *_ = _reveal_once(c, 1.0, L)
+    assert (masked[:L] == 0).sum() == 1 and masked[3] == 0           # lowest position wins the tie
+
+
+def test_reveal_monotone_in_tau_and_forced_minimum():
+    L = 16
+    conf = RNG.uniform(0, 1, 4 * L)
+    prev = None
+    for tau in (0.0, 0.2, 0.5, 0.8, 0.95, 1.0):
+        masked, *_ = _reveal_once(conf, tau, L)
+        revealed = masked == 0
+        for b in range(4):
+            blk = slice(b * L, (b + 1) * L)
+            expect = conf[blk] > tau
+            if not expect.any():
+                expect = np.zeros(L, bool); expect[np.argmax(conf[blk])] = True
+            np.testing.assert_array_equal(revealed[blk], expect)
+        if prev is not None:
+            assert np.all(revealed <= prev)                          # revealed set shrinks as tau grows
+        prev = revealed
+    # static decoding: tau = 1, r_min = r reveals exactly the r most confident masked rows
+    pre = np.ones(4 * L, np.uint8); pre[::3] = 0
+    masked, ra, *_ = _reveal_once(conf, 1.0, L, r_min=3, masked=pre)
+    for b in range(4):
+        blk = np.arange(b * L, (b + 1) * L)
+        cand = blk[pre[blk] == 1]
+        want = set(cand[np.argsort(-conf[cand], kind="stable")[:3]])
+        got = set(blk[(pre[blk] == 1) & (masked[blk] == 0)])
+        assert got == want
+    # a sequence with nothing masked reveals nothing and keeps its conditioning token
+    none = np.zeros(L, np.uint8)
+    masked, ra, dp, dt, cond, _ = _reveal_once(conf[:L], 0.0, L, masked=none)
+    assert dp[0] == -1 and dt[0] == -1 and cond[0] == 7 and np.all(ra == -1)
+
+
+def test_max_accept_cap_values_and_effect():
+    with open(os.path.join(HERE, "golden", "max_accept_cap.txt")) as f:
+        rows = [tuple(map(int, ln.split())) for ln in f if ln.strip() and not ln.startswith("#")]
+    assert len(rows) >= 10
+    for n, L, m in rows:
+        assert orc.max_accept_cap(n, L) == m
+    L = 16
+    conf = RNG.uniform(0.6, 0.99, L)
+    masked, *_ = _reveal_once(conf, 0.5, L, max_accept=1)             # all 16 clear tau, cap is 11
+    assert (masked == 0).sum() == 11
+    keep = np.argsort(-conf, kind="stable")[:11]
+    assert np.all(masked[keep] == 0)
+    masked, *_ = _reveal_once(conf, 0.5, L, max_accept=0)
+    assert (masked == 0).sum() == 16
+
+
+# ------------------------------------------------------------------ verify
+def test_verify_accept_is_longest_matching_prefix_bruteforce():
+    B, L = 1, 4
+    for V in (4, 8, 16):
+        for K in (1, 2, 3):
+            for pattern in itertools.product([0, 1], repeat=K):
+                verify = RNG.normal(0, 2, (B, L, V)).astype(np.float32)
+                pos = RNG.permutation(L)[:K].astype(np.int32)
+                tok = np.empty(K, np.int32)
+                for j in range(K):
+                    best = int(np.argmax(verify[0, pos[j]]))
+                    tok[j] = best if pattern[j] else (best + 1 + RNG.integers(0, V - 1)) % V
+                match, alen, corr = orc.verify_accept(verify, pos[None].copy(), tok[None].copy())
+                # brute force: the largest a such that every one of the first a drafts matches
+                brute = max(a for a in range(K + 1) if all(pattern[:a]))
+                assert alen[0] == brute
+                np.testing.assert_array_equal(match[0], np.array(pattern, np.uint8))
+                if brute < K:
+                    assert corr[0] == int(np.argmax(verify[0, pos[brute]]))
+                else:
+                    assert corr[0] == -1
+
+
+def test_verify_missing_draft_and_ties():
+    V, L = 8, 4
+    verify = np.zeros((2, L, V), np.float32)
+    verify[0, 2, 5] = 1.0
+    verify[1, 1, 3] = 2.0; verify[1, 1, 6] = 2.0                       # tie -> lowest index 3
+    pos = np.array([[2, -1, 0], [1, 0, 2]], np.int32)
+    tok = np.array([[5, -1, 0], [6, 0, 0]], np.int32)
+    match, alen, corr = orc.verify_accept(verify, pos, tok)
+    assert list(match[0]) == [1, 0, 1] and alen[0] == 1 and corr[0] == -1   # missing draft ends the prefix
+    assert list(match[1]) == [0, 1, 1] and alen[1] == 0 and corr[1] == 3
+
+
+# ------------------------------------------------------------------ remask
+def test_remask_set_inclusions():
+    B, L = 3, 8
+    M = B * L
+    conf = RNG.uniform(0, 1, M)
+    ra0 = RNG.integers(-2, 3, M).astype(np.int8)                       # -2 committed, -1 masked, 0..2 states
+    m0 = (ra0 == -1).astype(np.uint8)
+    protect = np.array([1, -1, 5], np.int32)
+    state = 2
+    elig = (ra0 >= 0) & (ra0 <= state - 1)
+    for b in range(B):
+        if protect[b] >= 0:
+            elig[b * L + protect[b]] = False
+    # tau_r = 0: nothing; tau_r > 1: every eligible row
+    for tau_r, want in ((0.0, np.zeros(M, bool)), (1.5, elig), (0.4, elig & (conf < 0.4))):
+        m, ra = m0.copy(), ra0.copy()
+        rem = orc.remask(B, L, state, conf, tau_r, protect, m, ra).astype(bool)
+        np.testing.assert_array_equal(rem, want)
+        assert np.all(rem <= elig)
+        np.testing.assert_array_equal(m, np.where(want, 1, m0))
+        np.testing.assert_array_equal(ra, np.where(want, -1, ra0))
+    # rows revealed by the current state are not eligible
+    ra = np.full(M, 2, np.int8); m = np.zeros(M, np.uint8)
+    assert orc.remask(B, L, 2, conf, 1.5, None, m, ra).sum() == 0
+
+
+def test_chain_remask_and_reveal_control_flow():
+    """Remask mode end to end on a straddling tiny case: the remasked rows are exactly the
+    earlier-revealed, unprotected rows whose updated confidence is below the remask threshold."""
+    cfg = mi.straddling(mi.config(0, B=6, L=8, V=512))
+    W, E = mi.lm_head(cfg), mi.embedding(cfg)
+    heads = [mi.head_weights(cfg, k) for k in range(cfg.K)]
+    z0, h = mi.logits0(cfg), mi.hidden(cfg)
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, tau=0.5, tau_remask=0.3)
+    out = orc.chain_step(oc, E, W, heads, z0, val(h))
+    # replay the mask life cycle from the per-state outputs
+    masked = np.ones(cfg.M, bool); ra = np.full(cfg.M, -1)
+    n_rem = 0
+    for k in range(cfg.K + 1):
+        conf = out.conf[k]
+        for b in range(cfg.B):
+            rows = np.arange(b * cfg.L, (b + 1) * cfg.L)
+            cand = rows[masked[rows]]
+            if len(cand) == 0:
+                assert out.draft_pos[b, k] == -1
+                continue
+            sel = cand[conf[cand] > 0.5]
+            if len(sel) == 0:
+                sel = cand[[np.argmax(conf[cand])]]
+            masked[sel] = False; ra[sel] = k
+            top = sel[np.argmax(conf[sel])]
+            assert out.draft_pos[b, k] == top - b * cfg.L
+            assert out.draft_tok[b, k] == out.tok[k][top]
+            if k == 0:
+                assert out.protect_pos[b] == top - b * cfg.L
+        if k > 0:
+            rem = (ra >= 0) & (ra <= k - 1) & (conf < 0.3)
+            rem[np.arange(cfg.B) * cfg.L + out.protect_pos] = False
+            np.testing.assert_array_equal(out.remasked[k].astype(bool), rem)
+            masked[rem] = True; ra[rem] = -1
+            n_rem += rem.sum()
+    np.testing.assert_array_equal(out.masked.astype(bool), masked)
+    np.testing.assert_array_equal(out.revealed_at, ra)
+    assert n_rem > 0 and (out.revealed_at == 0).sum() > cfg.B     # both branches were exercised
