@@ -1,0 +1,197 @@
+/*
+ * mrp.h — C ABI of the MI355X (gfx950) Multi-token Residual Prediction chain step.
+ *
+ * One denoising step of a block-diffusion LM with MRP (paper Section 3.4,
+ * Algorithms 2-4): after the backbone has produced hidden states h and logits z
+ * for the B x L rows of the current blocks, a chain of K lightweight heads
+ * repeatedly predicts a logit residual through the shared LM head, adds it to
+ * the logit state, and reduces every row over the vocabulary (softmax
+ * confidence = top-1 probability, argmax) to drive reveal, draft, remask and
+ * speculative accept decisions.
+ *
+ * Conventions
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller unless it
+ *     says "host".  The library allocates only the workspace inside mrp_ctx
+ *     (at mrp_create) and never allocates or synchronises in the calls below.
+ *   - `stream` is a hipStream_t passed as void*; all work is enqueued on it,
+ *     in order, and the call returns without waiting.
+ *   - Arguments are validated on the host before anything is launched; a
+ *     failed validation returns a negative status and launches nothing.
+ *   - Rows: M = B * L, row i belongs to sequence b = i / L, position p = i % L.
+ *   - bf16 tensors are raw 16-bit patterns.  "packed" bf16 matrices are in the
+ *     MFMA fragment order produced by mrp_pack_weight (see below).
+ *   - Ties: an argmax over the vocabulary takes the lowest index; "most
+ *     confident" ties take the lowest position.
+ */
+#ifndef MRP_H
+#define MRP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define MRP_OK 0
+#define MRP_ERR_NULL (-1)      /* a required pointer is NULL                      */
+#define MRP_ERR_SHAPE (-2)     /* a size is out of range or inconsistent          */
+#define MRP_ERR_ALIGN (-3)     /* a pointer is not 16-byte aligned                */
+#define MRP_ERR_WORKSPACE (-4) /* rows / sizes exceed what mrp_create reserved    */
+#define MRP_ERR_HIP (-5)       /* a HIP runtime call failed (see mrp_last_error)  */
+
+#define MRP_MAX_BLOCK_LEN 64
+#define MRP_MAX_HEADS 16
+
+typedef struct mrp_ctx mrp_ctx;
+
+/* Problem sizes fixed for the life of a context.
+ *   d          hidden size, multiple of 128
+ *   V          vocabulary size, >= 1 (any value; multiples of 4 take the
+ *              vectorised logit path)
+ *   max_rows   largest M = B * L any call will use
+ *   block_len  L, 1..MRP_MAX_BLOCK_LEN
+ *   rms_eps    epsilon inside the RMSNorm square root */
+typedef struct {
+    int d, V, max_rows, block_len;
+    float rms_eps;
+} mrp_dims;
+
+/* One head's weights (device).  W1: [d][2d], W2: [d][d], both packed with
+ * mrp_pack_weight; gamma: bf16 [d], plain.  Head body (benchmark layout
+ * standing in for the transformer layers of Section 3.2):
+ *   x = [h_run ; E[cond_tok]],  a = W1 x,  s = a * sigmoid(a),  u = W2 s,
+ *   h_run += u (hidden residual, Algorithm 2 line "h <- h + Delta"),
+ *   y = bf16(u / sqrt(mean(u^2) + eps) * gamma),  delta = W_lm y. */
+typedef struct {
+    const void *W1_packed, *W2_packed, *gamma;
+} mrp_head;
+
+/* Decision rules of one chain step.
+ *   tau          reveal every still-masked row with confidence > tau (strict;
+ *                Section 4.1 "Denoising Mode": dynamic denoising)
+ *   r_min        forced minimum number of reveals per sequence and state (the
+ *                paper's "minimum of one position"); static top-r decoding is
+ *                tau >= 1 with r_min = r (Algorithm 2)
+ *   max_accept   1: cap threshold reveals at min(max(floor(0.7 n), 5), L),
+ *                n = masked rows of the sequence (Section 4.4)
+ *   carry_hidden 1: h_run <- h_run + u between heads
+ *   tau_remask   >= 0: after each head, rows revealed earlier in this chain
+ *                step whose new confidence is < tau_remask (strict) are masked
+ *                again, except the protected state-0 top row (Algorithm 4 with
+ *                tau_remask = tau); < 0: off
+ *   head_reveal  1: apply the reveal rule after every head (Algorithms 2, 3);
+ *                0: only at state 0 (Algorithm 4)
+ *   fresh_block  1: state 0 treats every row as masked and resets revealed_at
+ *   state_offset index of the state that precedes the first head: the K heads
+ *                run as states state_offset+1 .. state_offset+K (0 for a whole
+ *                chain step; s to continue a step after its state s)
+ *   run_state0   1: first reduce z and apply the reveal rule as state
+ *                state_offset (the backbone's own reveal, Algorithm 2 line
+ *                before the inner loop); 0: skip it and take cond_tok /
+ *                protect_pos / masks as given */
+typedef struct {
+    float tau;
+    int r_min;
+    int max_accept;
+    int carry_hidden;
+    float tau_remask;
+    int head_reveal;
+    int fresh_block;
+    int state_offset;
+    int run_state0;
+} mrp_reveal_cfg;
+
+/* Per-step state and outputs (device).  Slot k of tok/conf/lse is the local
+ * state index: 0 = state 0 (untouched when run_state0 = 0), k = after head k.
+ *   tok, conf, lse   [(K+1)][M]  argmax, top-1 probability, log-sum-exp; required
+ *   revealed_at      [M] in/out  -1 masked, -2 committed in an earlier step,
+ *                                else the state index that revealed the row
+ *   masked           [M] in/out  1 = still [MASK]
+ *   cond_tok         [B] in/out  token that conditions the next head: the token
+ *                                of the most confident row revealed by the
+ *                                previous state (kept if nothing was revealed)
+ *   protect_pos      [B] in/out  position of the state-0 top row (-1 if none);
+ *                                written at state 0, read by remask
+ *   draft_pos/tok    [B][K+1]    most confident new reveal of each local state
+ *                                (position in block, token), -1 if none
+ *   remasked         [(K+1)][M]  1 where a row was remasked at that state; may
+ *                                be NULL */
+typedef struct {
+    int32_t *tok;
+    float *conf;
+    float *lse;
+    int8_t *revealed_at;
+    uint8_t *masked;
+    int32_t *cond_tok;
+    int32_t *protect_pos;
+    int32_t *draft_pos, *draft_tok;
+    uint8_t *remasked;
+} mrp_step_io;
+
+/* Create / destroy a context on the current device.  mrp_create allocates the
+ * workspace (see mrp_workspace_bytes) with hipMalloc and zero-fills it. */
+int mrp_create(mrp_ctx **out, const mrp_dims *dims);
+int mrp_destroy(mrp_ctx *ctx);
+size_t mrp_workspace_bytes(const mrp_dims *dims);
+/* Message of the last error on this context (host string, never NULL). */
+const char *mrp_last_error(const mrp_ctx *ctx);
+
+/* Packed layout of a row-major bf16 matrix X[rows][cols] (cols % 16 == 0):
+ * 1 KiB blocks of 32 rows x 16 columns ordered [row block][column block];
+ * inside a block, lane l (0..63) owns the 8 consecutive values
+ * X[32 rb + l % 32][16 cb + 8 (l / 32) .. + 7] — the operand order of the
+ * 32x32x16 bf16 MFMA, so a wavefront's load of a block is one contiguous
+ * 1 KiB read.  rows are padded to a multiple of 32 with zeros. */
+size_t mrp_packed_bytes(int rows, int cols);
+int mrp_pack_weight(void *stream, const void *src /* bf16 [rows][cols] */, int rows, int cols,
+                    void *dst /* mrp_packed_bytes(rows, cols), 16-B aligned */);
+
+/* One denoising step's chain (Algorithm 2 inner loop / Algorithm 3 drafting
+ * loop / Algorithm 4 with tau_remask): state 0 = reduce z and reveal, then for
+ * k = 1..K: head k, z += W_lm y (fused with the per-row online
+ * max / sum-exp / argmax), reveal [, remask].
+ *   h       bf16 [M][d] backbone hidden states, or NULL to continue from h_run
+ *   h_run   fp32 [M][d] running hidden state: overwritten from h when h is
+ *           given, otherwise read; updated in place when carry_hidden
+ *   E       bf16 [V][d] token embedding, plain row-major
+ *   W_lm_packed  the shared LM head [V][d], packed
+ *   heads   HOST array of K entries (the same entry K times = weight sharing)
+ *   z       fp32 [M][V] logit state, updated in place */
+int mrp_chain_step(mrp_ctx *ctx, void *stream, int B, int K, const void *h, float *h_run,
+                   const void *E, const void *W_lm_packed, const mrp_head *heads, float *z,
+                   const mrp_reveal_cfg *cfg, const mrp_step_io *io);
+
+/* Remask rule alone (Algorithm 4, last line of the loop body): rows with
+ * revealed_at in [0, state-1], other than protect_pos[b] (NULL = none), whose
+ * conf_new < tau_remask become masked again (masked = 1, revealed_at = -1).
+ * remasked_out [M] receives 1 for those rows and 0 elsewhere. */
+int mrp_remask(mrp_ctx *ctx, void *stream, int B, int state, const float *conf_new,
+               float tau_remask, const int32_t *protect_pos, int8_t *revealed_at,
+               uint8_t *masked, uint8_t *remasked_out);
+
+/* Speculative verification (Algorithm 3, "reject drafted positions where the
+ * argmaxes differ"): for each sequence b and draft j < K,
+ *   v_j = argmax_v verify[b][draft_pos[b][j]][v],  match[b][j] = (v_j == draft_tok[b][j]);
+ *   accept_len[b] = length of the longest all-matching prefix of the K drafts;
+ *   correction_tok[b] = v at the first non-matching draft (-1 if all matched or
+ *   that draft is missing).  A draft with pos < 0 is a non-match.
+ *   verify fp32 [B][L][V]; draft_pos/draft_tok int32 [B][K] with row stride
+ *   draft_stride (>= K) elements. */
+int mrp_verify_accept(mrp_ctx *ctx, void *stream, int B, int K, const float *verify,
+                      const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride,
+                      uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
+                      int32_t *correction_tok /* [B] */);
+
+/* Timing of the dominant kernel.  With profiling on, every LM-head kernel
+ * launched by mrp_chain_step is bracketed by a pair of HIP events on the call's
+ * stream (up to 4096 pairs between reads).  mrp_profile_read waits for the
+ * recorded events, stores up to `cap` elapsed times in milliseconds into the
+ * HOST array ms_out, returns how many it stored, and clears the record. */
+int mrp_profile_enable(mrp_ctx *ctx, int on);
+int mrp_profile_read(mrp_ctx *ctx, float *ms_out, int cap);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MRP_H */

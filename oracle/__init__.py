@@ -30,7 +30,8 @@ class _Cfg(C.Structure):
     _fields_ = [("d", C.c_int), ("V", C.c_int), ("B", C.c_int), ("L", C.c_int), ("K", C.c_int),
                 ("rms_eps", C.c_double), ("tau", C.c_double), ("r_min", C.c_int),
                 ("max_accept", C.c_int), ("carry_hidden", C.c_int), ("tau_remask", C.c_double),
-                ("head_reveal", C.c_int), ("fresh_block", C.c_int), ("state_offset", C.c_int)]
+                ("head_reveal", C.c_int), ("fresh_block", C.c_int), ("state_offset", C.c_int),
+                ("run_state0", C.c_int)]
 
 
 _lib = None
@@ -59,9 +60,9 @@ def _chk(a, dtype, shape=None):
 
 
 def make_cfg(d, V, B, L, K, tau=0.9, r_min=1, max_accept=0, carry_hidden=1, tau_remask=-1.0,
-             head_reveal=1, fresh_block=1, state_offset=0, rms_eps=1e-6) -> _Cfg:
+             head_reveal=1, fresh_block=1, state_offset=0, run_state0=1, rms_eps=1e-6) -> _Cfg:
     return _Cfg(d, V, B, L, K, rms_eps, tau, r_min, max_accept, carry_hidden, tau_remask,
-                head_reveal, fresh_block, state_offset)
+                head_reveal, fresh_block, state_offset, run_state0)
 
 
 def bf16_round(x: np.ndarray) -> np.ndarray:
@@ -75,12 +76,13 @@ def max_accept_cap(n_masked: int, L: int) -> int:
     return lib().orc_max_accept_cap(n_masked, L)
 
 
-def reduce_rows(z: np.ndarray):
+def reduce_rows(z: np.ndarray, with_gap: bool = False):
     z = _chk(z, np.float64)
     M, V = z.shape
     tok = np.empty(M, np.int32); conf = np.empty(M, np.float64); lse = np.empty(M, np.float64)
-    lib().orc_reduce_rows(_p(z), M, V, _p(tok), _p(conf), _p(lse))
-    return tok, conf, lse
+    gap = np.empty(M, np.float64) if with_gap else None
+    lib().orc_reduce_rows(_p(z), M, V, _p(tok), _p(conf), _p(lse), _p(gap))
+    return (tok, conf, lse, gap) if with_gap else (tok, conf, lse)
 
 
 def head_mlp(cfg: _Cfg, W1, W2, gamma, E, cond_tok, hrun):
@@ -147,6 +149,7 @@ class ChainOut:
     draft_tok: np.ndarray
     remasked: np.ndarray     # [(K+1)][M]
     y: Optional[np.ndarray]  # [K][M][d] bf16-rounded LM-head operand
+    gap: np.ndarray          # [(K+1)][M] top-2 logit gap of every state
 
 
 def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, revealed_at=None,
@@ -172,7 +175,8 @@ def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, reveal
     dpos = np.empty((B, K + 1), np.int32); dtok = np.empty((B, K + 1), np.int32)
     rem = np.zeros((K + 1, M), np.uint8)
     y = np.empty((K, M, d)) if dump_y else None
+    gap = np.full((K + 1, M), np.inf)
     lib().orc_chain_step(C.byref(cfg), _p(E), _p(W_lm), w1s, w2s, gs, _p(z), _p(hrun), _p(tok), _p(conf),
                          _p(lse), _p(masked), _p(revealed_at), _p(cond_tok), _p(protect_pos), _p(dpos),
-                         _p(dtok), _p(rem), _p(y))
-    return ChainOut(z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos, dpos, dtok, rem, y)
+                         _p(dtok), _p(rem), _p(y), _p(gap))
+    return ChainOut(z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos, dpos, dtok, rem, y, gap)

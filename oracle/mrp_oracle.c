@@ -59,7 +59,8 @@ typedef struct {
     double tau_remask;   /* < 0: no remask                                    */
     int head_reveal;     /* 1: reveal after every head (Alg. 2/3); 0: Alg. 4 */
     int fresh_block;     /* 1: state 0 starts from an all-masked block       */
-    int state_offset;    /* 0: run state 0; s > 0: resume after state s      */
+    int state_offset;    /* heads run as states offset+1 .. offset+K          */
+    int run_state0;      /* 1: reduce z and reveal (state 0) before the heads */
 } orc_cfg;
 
 static double bf16_bits_to_double(uint16_t b) {
@@ -84,8 +85,10 @@ void orc_bf16_round_array(const double *x, double *out, long n) {
 }
 
 /* Per row: m = max, s = sum exp(z - m), tok = lowest index attaining m,
- * conf = 1/s (top-1 probability), lse = m + log s. */
-void orc_reduce_rows(const double *z, int M, int V, int32_t *tok, double *conf, double *lse) {
+ * conf = 1/s (top-1 probability), lse = m + log s.  gap (may be NULL) receives
+ * the top-2 logit gap: m minus the largest entry at any other index. */
+void orc_reduce_rows(const double *z, int M, int V, int32_t *tok, double *conf, double *lse,
+                     double *gap) {
 #pragma omp parallel for schedule(static)
     for (int i = 0; i < M; ++i) {
         const double *r = z + (size_t)i * V;
@@ -98,6 +101,12 @@ void orc_reduce_rows(const double *z, int M, int V, int32_t *tok, double *conf, 
         tok[i] = am;
         conf[i] = 1.0 / s;
         lse[i] = m + log(s);
+        if (gap) {
+            double second = -INFINITY;
+            for (int v = 0; v < V; ++v)
+                if (v != am && r[v] > second) second = r[v];
+            gap[i] = m - second;
+        }
     }
 }
 
@@ -268,13 +277,14 @@ void orc_verify_accept(int B, int L, int V, int K, const float *verify, const in
  *   masked, revealed_at [M] in/out; cond_tok, protect_pos [B] in/out
  *   draft_pos/draft_tok [B][K+1] (column = local state index)
  *   remasked [(K+1)][M] (may be NULL)
- *   y_dump  [K][M][d] (may be NULL) */
+ *   y_dump  [K][M][d] (may be NULL)
+ *   gap     [(K+1)][M] top-2 logit gap per state (may be NULL) */
 void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
                     const uint16_t *const *W1, const uint16_t *const *W2,
                     const uint16_t *const *gamma, double *z, double *hrun, int32_t *tok,
                     double *conf, double *lse, uint8_t *masked, int8_t *revealed_at,
                     int32_t *cond_tok, int32_t *protect_pos, int32_t *draft_pos,
-                    int32_t *draft_tok, uint8_t *remasked, double *y_dump) {
+                    int32_t *draft_tok, uint8_t *remasked, double *y_dump, double *gap) {
     const int M = c->B * c->L, K = c->K, B = c->B;
     int32_t *dp = (int32_t *)malloc(sizeof(int32_t) * B);
     int32_t *dt = (int32_t *)malloc(sizeof(int32_t) * B);
@@ -283,11 +293,11 @@ void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
         for (int k = 0; k <= K; ++k) { draft_pos[b * (K + 1) + k] = -1; draft_tok[b * (K + 1) + k] = -1; }
     if (remasked) memset(remasked, 0, (size_t)(K + 1) * M);
 
-    if (c->state_offset == 0) {
+    if (c->run_state0) {
         if (c->fresh_block)
             for (int i = 0; i < M; ++i) { masked[i] = 1; revealed_at[i] = -1; }
-        orc_reduce_rows(z, M, c->V, tok, conf, lse);
-        orc_reveal(c, 0, conf, tok, masked, revealed_at, dp, dt, cond_tok, protect_pos);
+        orc_reduce_rows(z, M, c->V, tok, conf, lse, gap);
+        orc_reveal(c, c->state_offset, conf, tok, masked, revealed_at, dp, dt, cond_tok, protect_pos);
         for (int b = 0; b < B; ++b) { draft_pos[b * (K + 1)] = dp[b]; draft_tok[b * (K + 1)] = dt[b]; }
     }
     for (int k = 1; k <= K; ++k) {
@@ -295,7 +305,8 @@ void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
         orc_head_mlp(c, W1[k - 1], W2[k - 1], gamma[k - 1], E, cond_tok, hrun, NULL, y);
         if (y_dump) memcpy(y_dump + (size_t)(k - 1) * M * c->d, y, sizeof(double) * (size_t)M * c->d);
         orc_lm_head_add(W_lm, y, z, M, c->V, c->d);
-        orc_reduce_rows(z, M, c->V, tok + (size_t)k * M, conf + (size_t)k * M, lse + (size_t)k * M);
+        orc_reduce_rows(z, M, c->V, tok + (size_t)k * M, conf + (size_t)k * M, lse + (size_t)k * M,
+                        gap ? gap + (size_t)k * M : NULL);
         if (c->head_reveal) {
             orc_reveal(c, state, conf + (size_t)k * M, tok + (size_t)k * M, masked, revealed_at,
                        dp, dt, cond_tok, NULL);

@@ -1,0 +1,227 @@
+"""ctypes binding of include/mrp.h — same names, argument marshalling only."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import List, Optional, Sequence
+
+from . import build as _build
+
+EXPORTED_SYMBOLS = [
+    "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
+    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_verify_accept",
+    "mrp_profile_enable", "mrp_profile_read",
+]
+
+MRP_MAX_HEADS = 16
+
+
+class MrpError(RuntimeError):
+    pass
+
+
+class _Dims(C.Structure):
+    _fields_ = [("d", C.c_int), ("V", C.c_int), ("max_rows", C.c_int), ("block_len", C.c_int),
+                ("rms_eps", C.c_float)]
+
+
+class _Head(C.Structure):
+    _fields_ = [("W1_packed", C.c_void_p), ("W2_packed", C.c_void_p), ("gamma", C.c_void_p)]
+
+
+class _RevealCfg(C.Structure):
+    _fields_ = [("tau", C.c_float), ("r_min", C.c_int), ("max_accept", C.c_int), ("carry_hidden", C.c_int),
+                ("tau_remask", C.c_float), ("head_reveal", C.c_int), ("fresh_block", C.c_int),
+                ("state_offset", C.c_int), ("run_state0", C.c_int)]
+
+
+class _StepIO(C.Structure):
+    _fields_ = [("tok", C.c_void_p), ("conf", C.c_void_p), ("lse", C.c_void_p), ("revealed_at", C.c_void_p),
+                ("masked", C.c_void_p), ("cond_tok", C.c_void_p), ("protect_pos", C.c_void_p),
+                ("draft_pos", C.c_void_p), ("draft_tok", C.c_void_p), ("remasked", C.c_void_p)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    """Load the built library (building it only if no library is present)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build(force=True)
+    lib = C.CDLL(_build.LIB)
+    lib.mrp_create.argtypes = [C.POINTER(C.c_void_p), C.POINTER(_Dims)]
+    lib.mrp_destroy.argtypes = [C.c_void_p]
+    lib.mrp_workspace_bytes.argtypes = [C.POINTER(_Dims)]
+    lib.mrp_workspace_bytes.restype = C.c_size_t
+    lib.mrp_last_error.argtypes = [C.c_void_p]
+    lib.mrp_last_error.restype = C.c_char_p
+    lib.mrp_packed_bytes.argtypes = [C.c_int, C.c_int]
+    lib.mrp_packed_bytes.restype = C.c_size_t
+    lib.mrp_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    lib.mrp_chain_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                   C.c_void_p, C.POINTER(_Head), C.c_void_p, C.POINTER(_RevealCfg),
+                                   C.POINTER(_StepIO)]
+    lib.mrp_remask.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_float, C.c_void_p,
+                               C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.mrp_verify_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.mrp_profile_enable.argtypes = [C.c_void_p, C.c_int]
+    lib.mrp_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
+    _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None stays NULL)."""
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise MrpError("tensor must be a contiguous device tensor")
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def packed_bytes(rows: int, cols: int) -> int:
+    return load_library().mrp_packed_bytes(rows, cols)
+
+
+def pack_weight(w):
+    """bf16 (or int16 bit pattern) device tensor [rows][cols] -> packed device tensor (uint8)."""
+    import torch
+    rows, cols = w.shape
+    n = packed_bytes(rows, cols)
+    if n == 0:
+        raise MrpError(f"cannot pack a {rows}x{cols} matrix (cols must be a multiple of 16)")
+    out = torch.empty(n, dtype=torch.uint8, device=w.device)
+    rc = load_library().mrp_pack_weight(_stream(), _ptr(w), rows, cols, _ptr(out))
+    if rc != 0:
+        raise MrpError(f"mrp_pack_weight failed: {rc}")
+    return out
+
+
+@dataclass
+class Head:
+    W1_packed: object
+    W2_packed: object
+    gamma: object
+
+
+@dataclass
+class RevealCfg:
+    tau: float = 0.9
+    r_min: int = 1
+    max_accept: int = 0
+    carry_hidden: int = 1
+    tau_remask: float = -1.0
+    head_reveal: int = 1
+    fresh_block: int = 1
+    state_offset: int = 0
+    run_state0: int = 1
+
+
+class StepIO:
+    """Device buffers of one chain step (allocated with torch)."""
+
+    def __init__(self, B: int, L: int, K: int, device="cuda"):
+        import torch
+        M = B * L
+        self.B, self.L, self.K = B, L, K
+        self.tok = torch.full((K + 1, M), -1, dtype=torch.int32, device=device)
+        self.conf = torch.zeros((K + 1, M), dtype=torch.float32, device=device)
+        self.lse = torch.zeros((K + 1, M), dtype=torch.float32, device=device)
+        self.revealed_at = torch.full((M,), -1, dtype=torch.int8, device=device)
+        self.masked = torch.ones((M,), dtype=torch.uint8, device=device)
+        self.cond_tok = torch.zeros((B,), dtype=torch.int32, device=device)
+        self.protect_pos = torch.full((B,), -1, dtype=torch.int32, device=device)
+        self.draft_pos = torch.full((B, K + 1), -1, dtype=torch.int32, device=device)
+        self.draft_tok = torch.full((B, K + 1), -1, dtype=torch.int32, device=device)
+        self.remasked = torch.zeros((K + 1, M), dtype=torch.uint8, device=device)
+
+    def c_struct(self) -> _StepIO:
+        return _StepIO(_ptr(self.tok), _ptr(self.conf), _ptr(self.lse), _ptr(self.revealed_at), _ptr(self.masked),
+                       _ptr(self.cond_tok), _ptr(self.protect_pos), _ptr(self.draft_pos), _ptr(self.draft_tok),
+                       _ptr(self.remasked))
+
+
+class MrpContext:
+    """Owns an ``mrp_ctx`` (workspace) for fixed (d, V, max_rows, block_len)."""
+
+    def __init__(self, d: int, V: int, max_rows: int, block_len: int, rms_eps: float = 1e-6):
+        import torch
+        if not torch.cuda.is_available():
+            raise MrpError("no GPU: the MRP chain has no CPU path")
+        self.lib = load_library()
+        self.d, self.V, self.max_rows, self.L = d, V, max_rows, block_len
+        self._dims = _Dims(d, V, max_rows, block_len, rms_eps)
+        h = C.c_void_p()
+        rc = self.lib.mrp_create(C.byref(h), C.byref(self._dims))
+        if rc != 0:
+            raise MrpError(f"mrp_create failed: {rc}")
+        self._h = h
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self.lib.mrp_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self) -> int:
+        return self.lib.mrp_workspace_bytes(C.byref(self._dims))
+
+    def last_error(self) -> str:
+        return self.lib.mrp_last_error(self._h).decode()
+
+    def _check(self, rc: int, what: str):
+        if rc < 0:
+            raise MrpError(f"{what} failed ({rc}): {self.last_error()}")
+        return rc
+
+    def chain_step(self, B: int, K: int, h, h_run, E, W_lm_packed, heads: Sequence[Head], z, cfg: RevealCfg,
+                   io: StepIO, check: bool = True) -> int:
+        harr = (_Head * max(len(heads), 1))(*[_Head(_ptr(x.W1_packed), _ptr(x.W2_packed), _ptr(x.gamma))
+                                              for x in heads])
+        if len(heads) < K <= MRP_MAX_HEADS:
+            raise MrpError("fewer heads than K")
+        ccfg = _RevealCfg(cfg.tau, cfg.r_min, cfg.max_accept, cfg.carry_hidden, cfg.tau_remask, cfg.head_reveal,
+                          cfg.fresh_block, cfg.state_offset, cfg.run_state0)
+        cio = io.c_struct()
+        rc = self.lib.mrp_chain_step(self._h, _stream(), B, K, _ptr(h), _ptr(h_run), _ptr(E), _ptr(W_lm_packed),
+                                     harr, _ptr(z), C.byref(ccfg), C.byref(cio))
+        return self._check(rc, "mrp_chain_step") if check else rc
+
+    def remask(self, B: int, state: int, conf_new, tau_remask: float, protect_pos, revealed_at, masked,
+               remasked_out, check: bool = True) -> int:
+        rc = self.lib.mrp_remask(self._h, _stream(), B, state, _ptr(conf_new), tau_remask, _ptr(protect_pos),
+                                 _ptr(revealed_at), _ptr(masked), _ptr(remasked_out))
+        return self._check(rc, "mrp_remask") if check else rc
+
+    def verify_accept(self, B: int, K: int, verify, draft_pos, draft_tok, draft_stride: int, match, accept_len,
+                      correction_tok, check: bool = True) -> int:
+        rc = self.lib.mrp_verify_accept(self._h, _stream(), B, K, _ptr(verify), _ptr(draft_pos), _ptr(draft_tok),
+                                        draft_stride, _ptr(match), _ptr(accept_len), _ptr(correction_tok))
+        return self._check(rc, "mrp_verify_accept") if check else rc
+
+    def profile_enable(self, on: bool):
+        self._check(self.lib.mrp_profile_enable(self._h, 1 if on else 0), "mrp_profile_enable")
+
+    def profile_read(self, cap: int = 4096) -> List[float]:
+        buf = (C.c_float * cap)()
+        n = self._check(self.lib.mrp_profile_read(self._h, buf, cap), "mrp_profile_read")
+        return [buf[i] for i in range(n)]

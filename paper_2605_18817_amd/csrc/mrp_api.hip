@@ -1,0 +1,344 @@
+// C ABI of libmrp (see include/mrp.h): context, argument validation and the
+// chain driver that enqueues one denoising step's K-head chain on one stream.
+#include "../../include/mrp.h"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <vector>
+
+#include "mrp_kernels.h"
+
+using namespace mrp;
+
+struct mrp_ctx {
+    mrp_dims dims;
+    int device;
+    int nIb;            // activation row blocks per k block (multiple of 8)
+    long plane;         // uint4 per activation plane
+    int nT_max;         // partial tiles per row
+    size_t part_rows;   // capacity of the k-split partial buffer, in rows of d floats
+    int maxB;
+    char *ws;
+    size_t ws_bytes;
+    uint4 *XH, *XE, *S, *Y;
+    float *PART, *pm, *ps;
+    int *pi;
+    float *vwm;
+    int *vwi;
+    char err[512];
+    bool prof_on;
+    std::vector<hipEvent_t> ev;  // pairs
+    int ev_used;
+};
+
+namespace {
+
+constexpr int PROF_PAIRS = 4096;
+
+size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+struct Layout {
+    int nIb;
+    long plane;
+    int nT_max;
+    size_t part_rows;
+    int maxB;
+    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, total;
+};
+
+bool dims_ok(const mrp_dims *d) {
+    return d && d->d >= 128 && d->d % 128 == 0 && d->d <= 8192 && d->V >= 1 && d->max_rows >= 1 &&
+           d->max_rows <= 65535 && d->block_len >= 1 && d->block_len <= MRP_MAX_BLOCK_LEN &&
+           d->max_rows % d->block_len == 0 && d->rms_eps >= 0.f;
+}
+
+Layout make_layout(const mrp_dims *dm) {
+    Layout l;
+    const int ib = (dm->max_rows + 31) / 32;
+    l.nIb = (ib + 7) / 8 * 8;
+    l.plane = (long)(dm->d / 16) * l.nIb * 64;
+    const int nT_lm = ((dm->V + 31) / 32 + WG_WAVES - 1) / WG_WAVES;
+    const int nT_0 = reduce_rows_tiles(dm->V);
+    l.nT_max = nT_lm > nT_0 ? nT_lm : nT_0;
+    l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 8 : (dm->max_rows < 1024 ? 1024 : dm->max_rows);
+    l.maxB = dm->max_rows / dm->block_len;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+    l.off_XH = take((size_t)NSPLIT * l.plane * 16);
+    l.off_XE = take((size_t)l.plane * 16);
+    l.off_S = take((size_t)NSPLIT * l.plane * 16);
+    l.off_Y = take((size_t)l.plane * 16);
+    l.off_PART = take(l.part_rows * dm->d * sizeof(float));
+    l.off_pm = take((size_t)l.nT_max * dm->max_rows * 4);
+    l.off_ps = take((size_t)l.nT_max * dm->max_rows * 4);
+    l.off_pi = take((size_t)l.nT_max * dm->max_rows * 4);
+    const size_t vw = (size_t)l.maxB * MRP_MAX_HEADS * verify_chunks(dm->V);
+    l.off_vwm = take(vw * 4);
+    l.off_vwi = take(vw * 4);
+    l.total = o;
+    return l;
+}
+
+int fail(mrp_ctx *c, int code, const char *fmt, ...) {
+    if (c) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(c->err, sizeof(c->err), fmt, ap);
+        va_end(ap);
+    }
+    return code;
+}
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+#define HIP_TRY(ctx, expr)                                                                      \
+    do {                                                                                        \
+        hipError_t e_ = (expr);                                                                 \
+        if (e_ != hipSuccess) return fail(ctx, MRP_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+    } while (0)
+
+// k splits for a partial-sum GEMM so that small row counts still fill the chip
+int pick_ksplit(int nVt, int nMg, int G, size_t part_rows, int M) {
+    int want = (512 + nVt * nMg - 1) / (nVt * nMg);
+    if (want > 8) want = 8;
+    if (want > G / 2) want = G / 2;
+    if ((size_t)want * M > part_rows) want = (int)(part_rows / M);
+    return want < 1 ? 1 : want;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t mrp_workspace_bytes(const mrp_dims *dims) {
+    if (!dims_ok(dims)) return 0;
+    return make_layout(dims).total;
+}
+
+int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
+    if (!out || !dims) return MRP_ERR_NULL;
+    *out = nullptr;
+    if (!dims_ok(dims)) return MRP_ERR_SHAPE;
+    mrp_ctx *c = new mrp_ctx();
+    c->dims = *dims;
+    c->err[0] = 0;
+    c->prof_on = false;
+    c->ev_used = 0;
+    const Layout l = make_layout(dims);
+    c->nIb = l.nIb; c->plane = l.plane; c->nT_max = l.nT_max; c->part_rows = l.part_rows; c->maxB = l.maxB;
+    c->ws_bytes = l.total;
+    if (hipGetDevice(&c->device) != hipSuccess || hipMalloc(reinterpret_cast<void **>(&c->ws), l.total) != hipSuccess ||
+        hipMemset(c->ws, 0, l.total) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        delete c;
+        return MRP_ERR_HIP;
+    }
+    c->XH = reinterpret_cast<uint4 *>(c->ws + l.off_XH);
+    c->XE = reinterpret_cast<uint4 *>(c->ws + l.off_XE);
+    c->S = reinterpret_cast<uint4 *>(c->ws + l.off_S);
+    c->Y = reinterpret_cast<uint4 *>(c->ws + l.off_Y);
+    c->PART = reinterpret_cast<float *>(c->ws + l.off_PART);
+    c->pm = reinterpret_cast<float *>(c->ws + l.off_pm);
+    c->ps = reinterpret_cast<float *>(c->ws + l.off_ps);
+    c->pi = reinterpret_cast<int *>(c->ws + l.off_pi);
+    c->vwm = reinterpret_cast<float *>(c->ws + l.off_vwm);
+    c->vwi = reinterpret_cast<int *>(c->ws + l.off_vwi);
+    *out = c;
+    return MRP_OK;
+}
+
+int mrp_destroy(mrp_ctx *c) {
+    if (!c) return MRP_ERR_NULL;
+    for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
+    (void)hipFree(c->ws);
+    delete c;
+    return MRP_OK;
+}
+
+const char *mrp_last_error(const mrp_ctx *c) { return c ? c->err : "null context"; }
+
+size_t mrp_packed_bytes(int rows, int cols) {
+    if (rows < 1 || cols < 16 || cols % 16) return 0;
+    return ((size_t)rows + 31) / 32 * 32 * (size_t)cols * 2;
+}
+
+int mrp_pack_weight(void *stream, const void *src, int rows, int cols, void *dst) {
+    if (!src || !dst) return MRP_ERR_NULL;
+    if (rows < 1 || cols < 16 || cols % 16) return MRP_ERR_SHAPE;
+    if (!aligned16(src) || !aligned16(dst)) return MRP_ERR_ALIGN;
+    hipError_t e = launch_pack_weight(static_cast<const uint16_t *>(src), rows, cols, static_cast<uint4 *>(dst),
+                                      static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? MRP_OK : MRP_ERR_HIP;
+}
+
+int mrp_profile_enable(mrp_ctx *c, int on) {
+    if (!c) return MRP_ERR_NULL;
+    if (on && c->ev.empty()) {
+        c->ev.resize(2 * PROF_PAIRS);
+        for (auto &e : c->ev) HIP_TRY(c, hipEventCreate(&e));
+    }
+    c->prof_on = on != 0;
+    c->ev_used = 0;
+    return MRP_OK;
+}
+
+int mrp_profile_read(mrp_ctx *c, float *ms_out, int cap) {
+    if (!c || !ms_out) return MRP_ERR_NULL;
+    int n = 0;
+    for (int p = 0; p < c->ev_used && n < cap; ++p) {
+        HIP_TRY(c, hipEventSynchronize(c->ev[2 * p + 1]));
+        HIP_TRY(c, hipEventElapsedTime(&ms_out[n], c->ev[2 * p], c->ev[2 * p + 1]));
+        ++n;
+    }
+    c->ev_used = 0;
+    return n;
+}
+
+int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float *h_run, const void *E,
+                   const void *W_lm_packed, const mrp_head *heads, float *z, const mrp_reveal_cfg *cfg,
+                   const mrp_step_io *io) {
+    if (!c) return MRP_ERR_NULL;
+    if (!h_run || !E || !W_lm_packed || !z || !cfg || !io || (K > 0 && !heads))
+        return fail(c, MRP_ERR_NULL, "mrp_chain_step: required pointer is NULL");
+    if (!io->tok || !io->conf || !io->lse || !io->revealed_at || !io->masked || !io->cond_tok ||
+        !io->protect_pos || !io->draft_pos || !io->draft_tok)
+        return fail(c, MRP_ERR_NULL, "mrp_chain_step: required mrp_step_io pointer is NULL");
+    const int L = c->dims.block_len, d = c->dims.d, V = c->dims.V;
+    if (B < 0 || K < 0 || K > MRP_MAX_HEADS) return fail(c, MRP_ERR_SHAPE, "B=%d K=%d out of range", B, K);
+    if (cfg->r_min < 0 || cfg->state_offset < 0 || cfg->state_offset + K > 120 || !(cfg->tau == cfg->tau))
+        return fail(c, MRP_ERR_SHAPE, "bad reveal configuration");
+    const long Ml = (long)B * L;
+    if (Ml > c->dims.max_rows) return fail(c, MRP_ERR_WORKSPACE, "rows %ld exceed max_rows %d", Ml, c->dims.max_rows);
+    for (int k = 0; k < K; ++k) {
+        if (!heads[k].W1_packed || !heads[k].W2_packed || !heads[k].gamma)
+            return fail(c, MRP_ERR_NULL, "head %d has a NULL weight", k);
+        if (!aligned16(heads[k].W1_packed) || !aligned16(heads[k].W2_packed) || !aligned16(heads[k].gamma))
+            return fail(c, MRP_ERR_ALIGN, "head %d weights must be 16-byte aligned", k);
+    }
+    if ((h && !aligned16(h)) || !aligned16(h_run) || !aligned16(E) || !aligned16(W_lm_packed) || !aligned16(z))
+        return fail(c, MRP_ERR_ALIGN, "tensor base pointers must be 16-byte aligned");
+    if (B == 0) return MRP_OK;
+
+    const int M = (int)Ml;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const uint16_t *Eb = static_cast<const uint16_t *>(E);
+    const int IT = stream_gemm_it(M);
+    const int nMg = ((M + 31) / 32 + IT - 1) / IT;
+    const int off = cfg->state_offset;
+
+    SelectArgs sa;
+    memset(&sa, 0, sizeof(sa));
+    sa.pm = c->pm; sa.ps = c->ps; sa.pi = c->pi;
+    sa.M = M; sa.B = B; sa.L = L; sa.d = d; sa.V = V;
+    sa.tau = cfg->tau; sa.r_min = cfg->r_min; sa.max_accept = cfg->max_accept;
+    sa.revealed_at = io->revealed_at; sa.masked = io->masked;
+    sa.cond_tok = io->cond_tok; sa.protect_pos = io->protect_pos;
+    sa.draft_stride = K + 1;
+    sa.xe = c->XE; sa.nIb = c->nIb;
+
+    if (cfg->run_state0) {
+        int nT0 = 0;
+        HIP_TRY(c, launch_reduce_rows(z, M, V, c->pm, c->ps, c->pi, &nT0, st));
+        sa.nT = nT0;
+        sa.state = off; sa.do_reveal = 1; sa.fresh = cfg->fresh_block; sa.write_protect = 1;
+        sa.tau_remask = -1.f;
+        sa.tok = io->tok; sa.conf = io->conf; sa.lse = io->lse;
+        sa.draft_pos = io->draft_pos; sa.draft_tok = io->draft_tok;
+        sa.remasked = io->remasked;
+        sa.E = K > 0 ? Eb : nullptr;
+        HIP_TRY(c, launch_merge_select(sa, st));
+    } else if (K > 0) {
+        HIP_TRY(c, launch_gather_e(Eb, io->cond_tok, c->XE, c->nIb, B, L, d, V, st));
+    }
+    if (K == 0) return MRP_OK;
+
+    HIP_TRY(c, launch_init_hidden(static_cast<const uint16_t *>(h), h_run, c->XH, c->plane, c->nIb, M, d,
+                                  h != nullptr, st));
+    int np_h = h ? 1 : NSPLIT;
+    const int nkr_d = d / (16 * KSTEP);
+
+    for (int k = 1; k <= K; ++k) {
+        const mrp_head &hd = heads[k - 1];
+        StreamGemmArgs g;
+        // a = W1 [h_run ; e]
+        memset(&g, 0, sizeof(g));
+        g.Wp = static_cast<const uint4 *>(hd.W1_packed);
+        g.KBw = 2 * d / 16; g.n_rb = d / 32; g.nIb = c->nIb; g.M = M; g.R = d;
+        g.seg[0] = ActSeg{c->XH, c->plane, nkr_d, np_h};
+        g.seg[1] = ActSeg{c->XE, 0, nkr_d, 1};
+        g.nseg = 2;
+        g.nVt = d / WG_ROWS; g.nMg = nMg; g.G = 2 * nkr_d;
+        g.nKs = pick_ksplit(g.nVt, nMg, g.G, c->part_rows, M);
+        g.out = c->PART;
+        HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
+        HIP_TRY(c, launch_silu_split(c->PART, g.nKs, c->S, c->plane, c->nIb, M, d, st));
+        // u = W2 s
+        memset(&g, 0, sizeof(g));
+        g.Wp = static_cast<const uint4 *>(hd.W2_packed);
+        g.KBw = d / 16; g.n_rb = d / 32; g.nIb = c->nIb; g.M = M; g.R = d;
+        g.seg[0] = ActSeg{c->S, c->plane, nkr_d, NSPLIT};
+        g.nseg = 1;
+        g.nVt = d / WG_ROWS; g.nMg = nMg; g.G = nkr_d;
+        g.nKs = pick_ksplit(g.nVt, nMg, g.G, c->part_rows, M);
+        g.out = c->PART;
+        HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
+        // h_run += u ; y = bf16(RMSNorm(u) * gamma)
+        HIP_TRY(c, launch_norm(c->PART, g.nKs, static_cast<const uint16_t *>(hd.gamma), c->dims.rms_eps, h_run,
+                               cfg->carry_hidden != 0, c->Y, c->XH, c->plane, c->nIb, M, d, st));
+        if (cfg->carry_hidden) np_h = NSPLIT;
+        // z += W_lm y, fused with the split-vocabulary (max, sum-exp, argmax) partials
+        memset(&g, 0, sizeof(g));
+        g.Wp = static_cast<const uint4 *>(W_lm_packed);
+        g.KBw = d / 16; g.n_rb = (V + 31) / 32; g.nIb = c->nIb; g.M = M; g.R = V;
+        g.seg[0] = ActSeg{c->Y, 0, nkr_d, 1};
+        g.nseg = 1;
+        g.nVt = (g.n_rb + WG_WAVES - 1) / WG_WAVES; g.nMg = nMg; g.nKs = 1; g.G = nkr_d;
+        g.z = z; g.pm = c->pm; g.ps = c->ps; g.pi = c->pi;
+        const bool prof = c->prof_on && c->ev_used < PROF_PAIRS;
+        if (prof) HIP_TRY(c, hipEventRecord(c->ev[2 * c->ev_used], st));
+        HIP_TRY(c, launch_stream_gemm(g, EPI_LM, st));
+        if (prof) {
+            HIP_TRY(c, hipEventRecord(c->ev[2 * c->ev_used + 1], st));
+            ++c->ev_used;
+        }
+        // merge partials, reveal / draft / remask, gather the next conditioning embedding
+        sa.nT = g.nVt;
+        sa.state = off + k; sa.do_reveal = cfg->head_reveal; sa.fresh = 0; sa.write_protect = 0;
+        sa.tau_remask = cfg->tau_remask;
+        sa.tok = io->tok + (size_t)k * M; sa.conf = io->conf + (size_t)k * M; sa.lse = io->lse + (size_t)k * M;
+        sa.draft_pos = io->draft_pos + k; sa.draft_tok = io->draft_tok + k;
+        sa.remasked = io->remasked ? io->remasked + (size_t)k * M : nullptr;
+        sa.E = k < K ? Eb : nullptr;
+        HIP_TRY(c, launch_merge_select(sa, st));
+    }
+    return MRP_OK;
+}
+
+int mrp_remask(mrp_ctx *c, void *stream, int B, int state, const float *conf_new, float tau_remask,
+               const int32_t *protect_pos, int8_t *revealed_at, uint8_t *masked, uint8_t *remasked_out) {
+    if (!c) return MRP_ERR_NULL;
+    if (!conf_new || !revealed_at || !masked || !remasked_out) return fail(c, MRP_ERR_NULL, "mrp_remask: NULL pointer");
+    if (B < 0 || (long)B * c->dims.block_len > c->dims.max_rows || state < 0 || state > 126)
+        return fail(c, MRP_ERR_SHAPE, "mrp_remask: B=%d state=%d out of range", B, state);
+    if (B == 0) return MRP_OK;
+    HIP_TRY(c, launch_remask(B, c->dims.block_len, state, conf_new, tau_remask, protect_pos, revealed_at, masked,
+                             remasked_out, static_cast<hipStream_t>(stream)));
+    return MRP_OK;
+}
+
+int mrp_verify_accept(mrp_ctx *c, void *stream, int B, int K, const float *verify, const int32_t *draft_pos,
+                      const int32_t *draft_tok, int draft_stride, uint8_t *match, int32_t *accept_len,
+                      int32_t *correction_tok) {
+    if (!c) return MRP_ERR_NULL;
+    if (!verify || !draft_pos || !draft_tok || !match || !accept_len || !correction_tok)
+        return fail(c, MRP_ERR_NULL, "mrp_verify_accept: NULL pointer");
+    if (B < 0 || B > c->maxB || K < 1 || K > MRP_MAX_HEADS || draft_stride < K || (long)B * K > 65535)
+        return fail(c, MRP_ERR_SHAPE, "mrp_verify_accept: B=%d K=%d stride=%d out of range", B, K, draft_stride);
+    if (c->dims.V % 4 == 0 && !aligned16(verify)) return fail(c, MRP_ERR_ALIGN, "verify must be 16-byte aligned");
+    if (B == 0) return MRP_OK;
+    HIP_TRY(c, launch_verify(B, c->dims.block_len, c->dims.V, K, verify, draft_pos, draft_tok, draft_stride, c->vwm,
+                             c->vwi, match, accept_len, correction_tok, static_cast<hipStream_t>(stream)));
+    return MRP_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,145 @@
+// Internal declarations shared by the HIP translation units of libmrp.
+// Nothing here is part of the C ABI (see include/mrp.h).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace mrp {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// Number of bf16 terms an fp32 activation is split into before it enters a
+// bf16 MFMA (hi + mid + lo reproduces the fp32 value to ~2^-25), so that the
+// head body is computed to fp32 accuracy although the matrix cores take bf16.
+constexpr int NSPLIT = 3;
+
+constexpr int MAX_L = 64;         // largest block length (rows per sequence)
+constexpr int KSTEP = 8;          // 16-wide k blocks per pipeline stage (128 k)
+constexpr int WG_WAVES = 4;       // wavefronts per workgroup of the stream GEMM
+constexpr int WG_ROWS = 32 * WG_WAVES;  // weight rows per workgroup tile
+
+// One K segment of the activation operand of the stream GEMM.  The operand is
+// the sum over `nplanes` packed bf16 planes; plane p of local k block kb, row
+// block ib lives at base + p * plane_stride + (kb * nIb + ib) * 64 (uint4 units).
+struct ActSeg {
+    const uint4 *base;
+    long plane_stride;
+    int nkr;       // k ranges (of KSTEP blocks) in this segment
+    int nplanes;
+};
+
+enum { EPI_PARTIAL = 0, EPI_LM = 1 };
+
+struct StreamGemmArgs {
+    const uint4 *Wp;   // packed weights [n_rb][KBw][64] uint4
+    int KBw;           // k blocks per weight row block
+    int n_rb;          // weight row blocks (padded rows / 32)
+    int nIb;           // activation row blocks per k block (allocation stride)
+    int M;             // valid activation rows
+    int R;             // valid weight rows (outputs per activation row)
+    ActSeg seg[2];
+    int nseg;
+    int nVt, nMg, nKs; // grid decomposition: weight tiles, row groups, k splits
+    int G;             // total k ranges = KBw / KSTEP
+    // EPI_PARTIAL: out[ks][M][R] fp32
+    float *out;
+    // EPI_LM: z [M][R] fp32 in/out; partials [nVt][M]
+    float *z;
+    float *pm, *ps;
+    int *pi;
+};
+
+// row-reduction partial: running max, sum of exp(x - max), index of the max
+struct Part {
+    float m, s;
+    int i;
+};
+
+__device__ __forceinline__ Part part_identity() { return {-INFINITY, 0.f, 0x7fffffff}; }
+
+// Merge two partials; equal maxima keep the lower index.
+__device__ __forceinline__ Part part_merge(Part a, Part b) {
+    const bool b_wins = (b.m > a.m) || (b.m == a.m && b.i < a.i);
+    const float mx = b_wins ? b.m : a.m;
+    const float sa = (a.m == -INFINITY) ? 0.f : a.s * __expf(a.m - mx);
+    const float sb = (b.m == -INFINITY) ? 0.f : b.s * __expf(b.m - mx);
+    return {mx, sa + sb, b_wins ? b.i : a.i};
+}
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
+    uint32_t u = __float_as_uint(x);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+__device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+
+// hi/mid/lo bf16 terms of an fp32 value (each remainder is exact in fp32)
+__device__ __forceinline__ void split3(float x, uint16_t &hi, uint16_t &mid, uint16_t &lo) {
+    hi = f32_to_bf16_rne(x);
+    const float r1 = x - bf16_to_f32(hi);
+    mid = f32_to_bf16_rne(r1);
+    const float r2 = r1 - bf16_to_f32(mid);
+    lo = f32_to_bf16_rne(r2);
+}
+
+// index (in uint4 units) of the 16-byte chunk holding X[row][8*c8 .. 8*c8+7]
+// inside an activation plane laid out [kb][ib][64 lanes]
+__device__ __forceinline__ size_t act_chunk_index(int row, int c8, int nIb) {
+    const int kb = c8 >> 1, half = c8 & 1;
+    return ((size_t)kb * nIb + (row >> 5)) * 64 + (row & 31) + 32 * half;
+}
+
+// ---- host-side launchers (defined in the .hip files) ----
+hipError_t launch_stream_gemm(const StreamGemmArgs &a, int epi, hipStream_t st);
+size_t stream_gemm_lds_bytes(int it);
+int stream_gemm_it(int M);   // activation row blocks per workgroup for M rows
+
+hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, hipStream_t st);
+hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb,
+                              int M, int d, bool from_h, hipStream_t st);
+hipError_t launch_gather_e(const uint16_t *E, const int32_t *cond_tok, uint4 *xe, int nIb, int B, int L,
+                           int d, int V, hipStream_t st);
+hipError_t launch_silu_split(const float *part, int nKs, uint4 *s_planes, long plane_stride, int nIb,
+                             int M, int d, hipStream_t st);
+hipError_t launch_norm(const float *part, int nKs, const uint16_t *gamma, float eps, float *hrun,
+                       bool carry, uint4 *y, uint4 *xh, long plane_stride, int nIb, int M, int d,
+                       hipStream_t st);
+
+struct SelectArgs {
+    const float *pm, *ps;
+    const int *pi;
+    int nT;                 // partial tiles per row
+    int M, B, L, d, V;
+    int state;              // global state index recorded in revealed_at
+    int do_reveal;          // apply the reveal rule at this state
+    int fresh;              // treat every row as masked first (state 0 of a fresh block)
+    int write_protect;      // record the top row in protect_pos (state 0)
+    float tau;
+    int r_min, max_accept;
+    float tau_remask;       // < 0: no remask at this state
+    int32_t *tok;
+    float *conf, *lse;      // this state's slots [M]
+    int8_t *revealed_at;
+    uint8_t *masked;
+    int32_t *cond_tok, *protect_pos;
+    int32_t *draft_pos, *draft_tok;  // this state's column, stride draft_stride
+    int draft_stride;
+    uint8_t *remasked;      // this state's slot [M] or nullptr
+    const uint16_t *E;      // embedding rows to gather for the next head (nullptr: skip)
+    uint4 *xe;
+    int nIb;
+};
+hipError_t launch_reduce_rows(const float *z, int M, int V, float *pm, float *ps, int *pi, int *nT_out,
+                              hipStream_t st);
+int reduce_rows_tiles(int V);
+hipError_t launch_merge_select(const SelectArgs &a, hipStream_t st);
+hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_remask,
+                         const int32_t *protect_pos, int8_t *revealed_at, uint8_t *masked,
+                         uint8_t *remasked, hipStream_t st);
+hipError_t launch_verify(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
+                         const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
+                         int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
+int verify_chunks(int V);
+
+}  // namespace mrp

@@ -1,0 +1,326 @@
+// Vocabulary reductions and the per-sequence decision logic of the MRP chain:
+//   reduce_rows    state 0: split-vocabulary (max, sum-exp, argmax) partials of z
+//   merge_select   merge a row's partials into (token, confidence, log-sum-exp)
+//                  — confidence is the top-1 softmax probability (paper
+//                  Section 2) — then, one workgroup per sequence, apply the
+//                  reveal rule (threshold with a forced minimum, Section 4.1;
+//                  optional max-accept cap, Section 4.4), record the draft
+//                  (Algorithm 3: most confident new reveal), optionally remask
+//                  (Algorithm 4) and gather the embedding row that conditions
+//                  the next head
+//   remask         Algorithm 4's remask rule on its own
+//   verify         Algorithm 3's accept test: argmax of the verifier's logits at
+//                  the drafted positions, longest matching prefix
+#include "mrp_kernels.h"
+
+namespace mrp {
+
+namespace {
+
+constexpr int RT = 8192;  // vocabulary entries per workgroup in the plain row reductions
+
+__device__ __forceinline__ Part wave_merge(Part p) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        Part o;
+        o.m = __shfl_xor(p.m, off);
+        o.s = __shfl_xor(p.s, off);
+        o.i = __shfl_xor(p.i, off);
+        p = part_merge(p, o);
+    }
+    return p;
+}
+
+// all 256 threads call; result valid in thread 0
+__device__ __forceinline__ Part block_merge(Part p, float *sm, float *ss, int *si) {
+    p = wave_merge(p);
+    const int wave = threadIdx.x >> 6;
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) { sm[wave] = p.m; ss[wave] = p.s; si[wave] = p.i; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        p = Part{sm[0], ss[0], si[0]};
+        for (int w = 1; w < 4; ++w) p = part_merge(p, Part{sm[w], ss[w], si[w]});
+    }
+    return p;
+}
+
+template <bool VEC4>
+__global__ __launch_bounds__(256) void reduce_rows_kernel(const float *__restrict__ z, int M, int V,
+                                                          float *__restrict__ pm, float *__restrict__ ps,
+                                                          int *__restrict__ pi) {
+    __shared__ float sm[4], ss[4];
+    __shared__ int si[4];
+    const int t = blockIdx.x, i = blockIdx.y;
+    const float *row = z + (size_t)i * V;
+    const int v0 = t * RT;
+    float x[32];
+    if constexpr (VEC4) {
+#pragma unroll
+        for (int n = 0; n < 8; ++n) {
+            const int v = v0 + 4 * (threadIdx.x + 256 * n);
+            float4 q = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+            if (v < V) q = *reinterpret_cast<const float4 *>(row + v);
+            x[4 * n] = q.x; x[4 * n + 1] = q.y; x[4 * n + 2] = q.z; x[4 * n + 3] = q.w;
+        }
+    } else {
+#pragma unroll
+        for (int n = 0; n < 32; ++n) {
+            const int v = v0 + threadIdx.x + 256 * n;
+            x[n] = (v < V) ? row[v] : -INFINITY;
+        }
+    }
+    Part p = part_identity();
+#pragma unroll
+    for (int n = 0; n < 32; ++n) {
+        const int v = VEC4 ? v0 + 4 * (threadIdx.x + 256 * (n >> 2)) + (n & 3) : v0 + threadIdx.x + 256 * n;
+        if (x[n] > p.m) { p.m = x[n]; p.i = v; }
+    }
+    float s = 0.f;
+    if (p.m > -INFINITY) {
+#pragma unroll
+        for (int n = 0; n < 32; ++n) s += __expf(x[n] - p.m);  // exp(-inf) = 0 for padding
+    }
+    p.s = s;
+    p = block_merge(p, sm, ss, si);
+    if (threadIdx.x == 0) {
+        pm[(size_t)t * M + i] = p.m;
+        ps[(size_t)t * M + i] = p.s;
+        pi[(size_t)t * M + i] = p.i;
+    }
+}
+
+__device__ __forceinline__ bool more_confident(const float *conf, int a, int b) {
+    if (conf[a] != conf[b]) return conf[a] > conf[b];
+    return a < b;
+}
+
+__global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
+    __shared__ float sm[4], ss[4];
+    __shared__ int si[4];
+    __shared__ float s_conf[MAX_L];
+    __shared__ int s_tok[MAX_L];
+    __shared__ int s_gather;  // 1: cond_tok changed or must be (re)gathered
+    const int b = blockIdx.x, L = a.L;
+
+    for (int p = 0; p < L; ++p) {
+        const int i = b * L + p;
+        Part pt = part_identity();
+        for (int t = threadIdx.x; t < a.nT; t += 256)
+            pt = part_merge(pt, Part{a.pm[(size_t)t * a.M + i], a.ps[(size_t)t * a.M + i], a.pi[(size_t)t * a.M + i]});
+        pt = block_merge(pt, sm, ss, si);
+        if (threadIdx.x == 0) {
+            const float conf = 1.0f / pt.s;
+            a.tok[i] = pt.i;
+            a.conf[i] = conf;
+            a.lse[i] = pt.m + logf(pt.s);
+            s_conf[p] = conf;
+            s_tok[p] = pt.i;
+        }
+    }
+    __syncthreads();
+
+    if (threadIdx.x == 0) {
+        uint8_t mk[MAX_L];
+        int8_t ra[MAX_L];
+        int cand[MAX_L];
+        for (int p = 0; p < L; ++p) {
+            mk[p] = a.fresh ? (uint8_t)1 : a.masked[b * L + p];
+            ra[p] = a.fresh ? (int8_t)-1 : a.revealed_at[b * L + p];
+        }
+        int dpos = -1, dtok = -1;
+        if (a.do_reveal) {
+            int nc = 0;
+            for (int p = 0; p < L; ++p)
+                if (mk[p]) cand[nc++] = p;
+            for (int x = 1; x < nc; ++x) {  // most confident first
+                const int p = cand[x];
+                int q = x - 1;
+                while (q >= 0 && more_confident(s_conf, p, cand[q])) { cand[q + 1] = cand[q]; --q; }
+                cand[q + 1] = p;
+            }
+            int ns = 0;
+            while (ns < nc && s_conf[cand[ns]] > a.tau) ++ns;
+            if (a.max_accept) {
+                int m = (7 * nc) / 10;
+                if (m < 5) m = 5;
+                if (m > L) m = L;
+                if (ns > m) ns = m;
+            }
+            if (ns < a.r_min) ns = a.r_min < nc ? a.r_min : nc;
+            for (int x = 0; x < ns; ++x) { mk[cand[x]] = 0; ra[cand[x]] = (int8_t)a.state; }
+            if (ns > 0) {
+                dpos = cand[0];
+                dtok = s_tok[cand[0]];
+                a.cond_tok[b] = dtok;
+            }
+            if (a.write_protect) a.protect_pos[b] = dpos;
+        }
+        a.draft_pos[(size_t)b * a.draft_stride] = dpos;
+        a.draft_tok[(size_t)b * a.draft_stride] = dtok;
+        const int prot = a.protect_pos[b];
+        for (int p = 0; p < L; ++p) {
+            uint8_t rem = 0;
+            if (a.tau_remask >= 0.f) {
+                const int r = ra[p];
+                if (r >= 0 && r <= a.state - 1 && p != prot && s_conf[p] < a.tau_remask) {
+                    mk[p] = 1; ra[p] = -1; rem = 1;
+                }
+            }
+            if (a.remasked) a.remasked[b * L + p] = rem;
+            a.masked[b * L + p] = mk[p];
+            a.revealed_at[b * L + p] = ra[p];
+        }
+        s_gather = a.cond_tok[b];
+    }
+    __syncthreads();
+
+    if (a.E != nullptr) {  // embedding row that conditions the next head
+        const int C8 = a.d >> 3;
+        int tokc = s_gather;  // caller contract: 0 <= cond_tok < V; clamp so a bad value cannot fault
+        tokc = tokc < 0 ? 0 : (tokc >= a.V ? a.V - 1 : tokc);
+        const uint4 *erow = reinterpret_cast<const uint4 *>(a.E + (size_t)tokc * a.d);
+        for (int c8 = threadIdx.x; c8 < C8; c8 += 256) {
+            const uint4 v = erow[c8];
+            for (int p = 0; p < L; ++p) a.xe[act_chunk_index(b * L + p, c8, a.nIb)] = v;
+        }
+    }
+}
+
+__global__ __launch_bounds__(64) void remask_kernel(int B, int L, int state, const float *__restrict__ conf,
+                                                    float tau_remask, const int32_t *__restrict__ protect_pos,
+                                                    int8_t *__restrict__ revealed_at, uint8_t *__restrict__ masked,
+                                                    uint8_t *__restrict__ remasked) {
+    const int b = blockIdx.x, p = threadIdx.x;
+    if (p >= L) return;
+    const int i = b * L + p;
+    const int prot = protect_pos ? protect_pos[b] : -1;
+    const int r = revealed_at[i];
+    uint8_t rem = 0;
+    if (r >= 0 && r <= state - 1 && p != prot && conf[i] < tau_remask) {
+        masked[i] = 1;
+        revealed_at[i] = -1;
+        rem = 1;
+    }
+    remasked[i] = rem;
+}
+
+// argmax partial of one RT-wide chunk of the verifier row of draft (b, j)
+template <bool VEC4>
+__global__ __launch_bounds__(256) void verify_argmax_kernel(int L, int V, int K, const float *__restrict__ verify,
+                                                            const int32_t *__restrict__ draft_pos, int draft_stride,
+                                                            int nC, float *__restrict__ wm, int *__restrict__ wi) {
+    __shared__ float sm[4], ss[4];
+    __shared__ int si[4];
+    const int c = blockIdx.x, bk = blockIdx.y;
+    const int b = bk / K, j = bk % K;
+    int pos = draft_pos[(size_t)b * draft_stride + j];
+    if (pos >= L) pos = -1;  // caller contract: pos < L; an invalid position counts as a missing draft
+    Part p = part_identity();
+    if (pos >= 0) {  // uniform over the workgroup
+        const float *row = verify + ((size_t)b * L + pos) * V;
+        const int v0 = c * RT;
+        if constexpr (VEC4) {
+            float4 q[8];
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                const int v = v0 + 4 * (threadIdx.x + 256 * n);
+                q[n] = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+                if (v < V) q[n] = *reinterpret_cast<const float4 *>(row + v);
+            }
+#pragma unroll
+            for (int n = 0; n < 8; ++n) {
+                const int v = v0 + 4 * (threadIdx.x + 256 * n);
+                if (q[n].x > p.m) { p.m = q[n].x; p.i = v; }
+                if (q[n].y > p.m) { p.m = q[n].y; p.i = v + 1; }
+                if (q[n].z > p.m) { p.m = q[n].z; p.i = v + 2; }
+                if (q[n].w > p.m) { p.m = q[n].w; p.i = v + 3; }
+            }
+        } else {
+            for (int n = 0; n < 32; ++n) {
+                const int v = v0 + threadIdx.x + 256 * n;
+                const float x = (v < V) ? row[v] : -INFINITY;
+                if (x > p.m) { p.m = x; p.i = v; }
+            }
+        }
+    }
+    p = block_merge(p, sm, ss, si);
+    if (threadIdx.x == 0) {
+        wm[(size_t)bk * nC + c] = p.m;
+        wi[(size_t)bk * nC + c] = (pos >= 0) ? p.i : -1;
+    }
+}
+
+__global__ __launch_bounds__(256) void verify_accept_kernel(int B, int K, int nC, const float *__restrict__ wm,
+                                                            const int *__restrict__ wi,
+                                                            const int32_t *__restrict__ draft_tok, int draft_stride,
+                                                            uint8_t *__restrict__ match, int32_t *__restrict__ accept_len,
+                                                            int32_t *__restrict__ correction_tok) {
+    const int b = blockIdx.x * 256 + threadIdx.x;
+    if (b >= B) return;
+    int alen = 0, corr = -1;
+    bool open = true;
+    for (int j = 0; j < K; ++j) {
+        const size_t base = ((size_t)b * K + j) * nC;
+        float m = wm[base];
+        int vj = wi[base];
+        for (int c = 1; c < nC; ++c)
+            if (wm[base + c] > m) { m = wm[base + c]; vj = wi[base + c]; }
+        const bool ok = vj >= 0 && vj == draft_tok[(size_t)b * draft_stride + j];
+        match[(size_t)b * K + j] = ok ? 1 : 0;
+        if (open) {
+            if (ok) ++alen;
+            else { open = false; corr = vj; }
+        }
+    }
+    accept_len[b] = alen;
+    correction_tok[b] = corr;
+}
+
+}  // namespace
+
+int reduce_rows_tiles(int V) { return (V + RT - 1) / RT; }
+int verify_chunks(int V) { return (V + RT - 1) / RT; }
+
+hipError_t launch_reduce_rows(const float *z, int M, int V, float *pm, float *ps, int *pi, int *nT_out,
+                              hipStream_t st) {
+    const int nT = reduce_rows_tiles(V);
+    *nT_out = nT;
+    if (V % 4 == 0)
+        hipLaunchKernelGGL(reduce_rows_kernel<true>, dim3(nT, M), dim3(256), 0, st, z, M, V, pm, ps, pi);
+    else
+        hipLaunchKernelGGL(reduce_rows_kernel<false>, dim3(nT, M), dim3(256), 0, st, z, M, V, pm, ps, pi);
+    return hipGetLastError();
+}
+
+hipError_t launch_merge_select(const SelectArgs &a, hipStream_t st) {
+    hipLaunchKernelGGL(merge_select_kernel, dim3(a.B), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_remask,
+                         const int32_t *protect_pos, int8_t *revealed_at, uint8_t *masked, uint8_t *remasked,
+                         hipStream_t st) {
+    hipLaunchKernelGGL(remask_kernel, dim3(B), dim3(64), 0, st, B, L, state, conf, tau_remask, protect_pos,
+                       revealed_at, masked, remasked);
+    return hipGetLastError();
+}
+
+hipError_t launch_verify(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
+                         const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
+                         int32_t *accept_len, int32_t *correction_tok, hipStream_t st) {
+    const int nC = verify_chunks(V);
+    if (V % 4 == 0)
+        hipLaunchKernelGGL(verify_argmax_kernel<true>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, verify,
+                           draft_pos, draft_stride, nC, wm, wi);
+    else
+        hipLaunchKernelGGL(verify_argmax_kernel<false>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, verify,
+                           draft_pos, draft_stride, nC, wm, wi);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(verify_accept_kernel, dim3((B + 255) / 256), dim3(256), 0, st, B, K, nC, wm, wi,
+                       draft_tok, draft_stride, match, accept_len, correction_tok);
+    return hipGetLastError();
+}
+
+}  // namespace mrp
