@@ -72,6 +72,10 @@ def bf16_round(x: np.ndarray) -> np.ndarray:
     return out
 
 
+def threads() -> int:
+    return lib().orc_threads()
+
+
 def max_accept_cap(n_masked: int, L: int) -> int:
     return lib().orc_max_accept_cap(n_masked, L)
 

@@ -48,6 +48,9 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 typedef struct {
     int d, V, B, L, K;
@@ -62,6 +65,15 @@ typedef struct {
     int state_offset;    /* heads run as states offset+1 .. offset+K          */
     int run_state0;      /* 1: reduce z and reveal (state 0) before the heads */
 } orc_cfg;
+
+/* threads the parallel loops will use */
+int orc_threads(void) {
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 static double bf16_bits_to_double(uint16_t b) {
     uint32_t u = ((uint32_t)b) << 16;

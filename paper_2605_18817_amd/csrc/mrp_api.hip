@@ -4,6 +4,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <vector>
 
@@ -19,6 +20,8 @@ struct mrp_ctx {
     int nT_max;         // partial tiles per row
     size_t part_rows;   // capacity of the k-split partial buffer, in rows of d floats
     int maxB;
+    bool lm_persist;    // use the persistent LM-head kernel for M <= 128 (tuning switch, env MRP_LM_PERSIST)
+    int nCU;            // compute units of the device (workgroups of the persistent LM-head kernel)
     char *ws;
     size_t ws_bytes;
     uint4 *XH, *XE, *S, *Y;
@@ -53,7 +56,7 @@ bool dims_ok(const mrp_dims *d) {
            d->max_rows % d->block_len == 0 && d->rms_eps >= 0.f;
 }
 
-Layout make_layout(const mrp_dims *dm) {
+Layout make_layout(const mrp_dims *dm, int nCU) {
     Layout l;
     const int ib = (dm->max_rows + 31) / 32;
     l.nIb = (ib + 7) / 8 * 8;
@@ -61,6 +64,8 @@ Layout make_layout(const mrp_dims *dm) {
     const int nT_lm = ((dm->V + 31) / 32 + WG_WAVES - 1) / WG_WAVES;
     const int nT_0 = reduce_rows_tiles(dm->V);
     l.nT_max = nT_lm > nT_0 ? nT_lm : nT_0;
+    const int nT_p = nCU * lm_persist_pmax((dm->V + 31) / 32, nCU);
+    if (nT_p > l.nT_max) l.nT_max = nT_p;
     l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 8 : (dm->max_rows < 1024 ? 1024 : dm->max_rows);
     l.maxB = dm->max_rows / dm->block_len;
     size_t o = 0;
@@ -113,7 +118,9 @@ extern "C" {
 
 size_t mrp_workspace_bytes(const mrp_dims *dims) {
     if (!dims_ok(dims)) return 0;
-    return make_layout(dims).total;
+    int dev = 0, nCU = 256;
+    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&nCU, hipDeviceAttributeMultiprocessorCount, dev);
+    return make_layout(dims, nCU > 0 ? nCU : 256).total;
 }
 
 int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
@@ -125,10 +132,19 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     c->err[0] = 0;
     c->prof_on = false;
     c->ev_used = 0;
-    const Layout l = make_layout(dims);
+    {   // tuning switch: MRP_LM_PERSIST=0 routes M <= 128 through the generic stream GEMM
+        const char *e = getenv("MRP_LM_PERSIST");
+        c->lm_persist = !(e && e[0] == '0');
+    }
+    if (hipGetDevice(&c->device) != hipSuccess ||
+        hipDeviceGetAttribute(&c->nCU, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->nCU < 1) {
+        delete c;
+        return MRP_ERR_HIP;
+    }
+    const Layout l = make_layout(dims, c->nCU);
     c->nIb = l.nIb; c->plane = l.plane; c->nT_max = l.nT_max; c->part_rows = l.part_rows; c->maxB = l.maxB;
     c->ws_bytes = l.total;
-    if (hipGetDevice(&c->device) != hipSuccess || hipMalloc(reinterpret_cast<void **>(&c->ws), l.total) != hipSuccess ||
+    if (hipMalloc(reinterpret_cast<void **>(&c->ws), l.total) != hipSuccess ||
         hipMemset(c->ws, 0, l.total) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
         delete c;
         return MRP_ERR_HIP;
@@ -287,22 +303,37 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
                                cfg->carry_hidden != 0, c->Y, c->XH, c->plane, c->nIb, M, d, st));
         if (cfg->carry_hidden) np_h = NSPLIT;
         // z += W_lm y, fused with the split-vocabulary (max, sum-exp, argmax) partials
-        memset(&g, 0, sizeof(g));
-        g.Wp = static_cast<const uint4 *>(W_lm_packed);
-        g.KBw = d / 16; g.n_rb = (V + 31) / 32; g.nIb = c->nIb; g.M = M; g.R = V;
-        g.seg[0] = ActSeg{c->Y, 0, nkr_d, 1};
-        g.nseg = 1;
-        g.nVt = (g.n_rb + WG_WAVES - 1) / WG_WAVES; g.nMg = nMg; g.nKs = 1; g.G = nkr_d;
-        g.z = z; g.pm = c->pm; g.ps = c->ps; g.pi = c->pi;
         const bool prof = c->prof_on && c->ev_used < PROF_PAIRS;
         if (prof) HIP_TRY(c, hipEventRecord(c->ev[2 * c->ev_used], st));
-        HIP_TRY(c, launch_stream_gemm(g, EPI_LM, st));
+        int nT_lm = 0;
+        if (c->lm_persist && M <= 128 && V % 4 == 0) {
+            LmPersistArgs la;
+            memset(&la, 0, sizeof(la));
+            la.Wp = static_cast<const uint4 *>(W_lm_packed);
+            la.Y = c->Y;
+            la.KB = d / 16; la.n_rb = (V + 31) / 32; la.nIb = c->nIb;
+            la.M = M; la.V = V;
+            la.nWG = c->nCU; la.Pmax = lm_persist_pmax(la.n_rb, la.nWG);
+            la.z = z; la.pm = c->pm; la.ps = c->ps; la.pi = c->pi;
+            HIP_TRY(c, launch_lm_persist(la, st));
+            nT_lm = la.nWG * la.Pmax;
+        } else {
+            memset(&g, 0, sizeof(g));
+            g.Wp = static_cast<const uint4 *>(W_lm_packed);
+            g.KBw = d / 16; g.n_rb = (V + 31) / 32; g.nIb = c->nIb; g.M = M; g.R = V;
+            g.seg[0] = ActSeg{c->Y, 0, nkr_d, 1};
+            g.nseg = 1;
+            g.nVt = (g.n_rb + WG_WAVES - 1) / WG_WAVES; g.nMg = nMg; g.nKs = 1; g.G = nkr_d;
+            g.z = z; g.pm = c->pm; g.ps = c->ps; g.pi = c->pi;
+            HIP_TRY(c, launch_stream_gemm(g, EPI_LM, st));
+            nT_lm = g.nVt;
+        }
         if (prof) {
             HIP_TRY(c, hipEventRecord(c->ev[2 * c->ev_used + 1], st));
             ++c->ev_used;
         }
         // merge partials, reveal / draft / remask, gather the next conditioning embedding
-        sa.nT = g.nVt;
+        sa.nT = nT_lm;
         sa.state = off + k; sa.do_reveal = cfg->head_reveal; sa.fresh = 0; sa.write_protect = 0;
         sa.tau_remask = cfg->tau_remask;
         sa.tok = io->tok + (size_t)k * M; sa.conf = io->conf + (size_t)k * M; sa.lse = io->lse + (size_t)k * M;

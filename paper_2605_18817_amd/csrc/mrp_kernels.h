@@ -50,6 +50,18 @@ struct StreamGemmArgs {
     int *pi;
 };
 
+// Persistent LM-head kernel (at most 128 activation rows, V % 4 == 0)
+struct LmPersistArgs {
+    const uint4 *Wp;   // packed W_lm [n_rb][KB][64]
+    const uint4 *Y;    // packed bf16 activation plane [KB][nIb][64]
+    int KB, n_rb, nIb;
+    int M, V;
+    int nWG, Pmax;     // workgroups (one per CU) and passes per workgroup
+    float *z;          // [M][V] in/out
+    float *pm, *ps;    // partials [nWG * Pmax][M]
+    int *pi;
+};
+
 // row-reduction partial: running max, sum of exp(x - max), index of the max
 struct Part {
     float m, s;
@@ -94,6 +106,10 @@ __device__ __forceinline__ size_t act_chunk_index(int row, int c8, int nIb) {
 hipError_t launch_stream_gemm(const StreamGemmArgs &a, int epi, hipStream_t st);
 size_t stream_gemm_lds_bytes(int it);
 int stream_gemm_it(int M);   // activation row blocks per workgroup for M rows
+
+hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st);
+size_t lm_persist_lds_bytes();
+int lm_persist_pmax(int n_rb, int nWG);
 
 hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, hipStream_t st);
 hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb,

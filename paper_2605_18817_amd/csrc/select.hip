@@ -96,20 +96,46 @@ __device__ __forceinline__ bool more_confident(const float *conf, int a, int b) 
 }
 
 __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
-    __shared__ float sm[4], ss[4];
-    __shared__ int si[4];
     __shared__ float s_conf[MAX_L];
     __shared__ int s_tok[MAX_L];
-    __shared__ int s_gather;  // 1: cond_tok changed or must be (re)gathered
+    __shared__ uint8_t s_mk[MAX_L], s_rem[MAX_L];
+    __shared__ int8_t s_ra[MAX_L];
+    __shared__ int s_gather;
     const int b = blockIdx.x, L = a.L;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
-    for (int p = 0; p < L; ++p) {
+    // state of the sequence: fetched up front so that its latency hides behind the merge
+    int in_cond = 0, in_prot = -1;
+    if (threadIdx.x < L) {
+        s_mk[threadIdx.x] = a.fresh ? (uint8_t)1 : a.masked[b * L + threadIdx.x];
+        s_ra[threadIdx.x] = a.fresh ? (int8_t)-1 : a.revealed_at[b * L + threadIdx.x];
+    }
+    if (threadIdx.x == 0) {
+        in_cond = a.cond_tok[b];
+        in_prot = a.write_protect ? -1 : a.protect_pos[b];
+    }
+
+    // one wavefront per row: merge the row's nT partials in a fixed order
+    for (int p = wave; p < L; p += 4) {
         const int i = b * L + p;
         Part pt = part_identity();
-        for (int t = threadIdx.x; t < a.nT; t += 256)
-            pt = part_merge(pt, Part{a.pm[(size_t)t * a.M + i], a.ps[(size_t)t * a.M + i], a.pi[(size_t)t * a.M + i]});
-        pt = block_merge(pt, sm, ss, si);
-        if (threadIdx.x == 0) {
+        for (int t0 = 0; t0 < a.nT; t0 += 64 * 4) {
+            float m[4], sx[4];
+            int ix[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {  // issue the loads of four strides before merging any
+                const int t = t0 + u * 64 + lane;
+                const bool ok = t < a.nT;
+                const size_t o = (size_t)(ok ? t : 0) * a.M + i;
+                m[u] = ok ? a.pm[o] : -INFINITY;
+                sx[u] = ok ? a.ps[o] : 0.f;
+                ix[u] = ok ? a.pi[o] : 0x7fffffff;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) pt = part_merge(pt, Part{m[u], sx[u], ix[u]});
+        }
+        pt = wave_merge(pt);
+        if (lane == 0) {
             const float conf = 1.0f / pt.s;
             a.tok[i] = pt.i;
             a.conf[i] = conf;
@@ -121,18 +147,12 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
     __syncthreads();
 
     if (threadIdx.x == 0) {
-        uint8_t mk[MAX_L];
-        int8_t ra[MAX_L];
         int cand[MAX_L];
-        for (int p = 0; p < L; ++p) {
-            mk[p] = a.fresh ? (uint8_t)1 : a.masked[b * L + p];
-            ra[p] = a.fresh ? (int8_t)-1 : a.revealed_at[b * L + p];
-        }
-        int dpos = -1, dtok = -1;
+        int dpos = -1, dtok = -1, cond = in_cond, prot = in_prot;
         if (a.do_reveal) {
             int nc = 0;
             for (int p = 0; p < L; ++p)
-                if (mk[p]) cand[nc++] = p;
+                if (s_mk[p]) cand[nc++] = p;
             for (int x = 1; x < nc; ++x) {  // most confident first
                 const int p = cand[x];
                 int q = x - 1;
@@ -148,33 +168,36 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
                 if (ns > m) ns = m;
             }
             if (ns < a.r_min) ns = a.r_min < nc ? a.r_min : nc;
-            for (int x = 0; x < ns; ++x) { mk[cand[x]] = 0; ra[cand[x]] = (int8_t)a.state; }
+            for (int x = 0; x < ns; ++x) { s_mk[cand[x]] = 0; s_ra[cand[x]] = (int8_t)a.state; }
             if (ns > 0) {
                 dpos = cand[0];
                 dtok = s_tok[cand[0]];
+                cond = dtok;
                 a.cond_tok[b] = dtok;
             }
-            if (a.write_protect) a.protect_pos[b] = dpos;
+            if (a.write_protect) { prot = dpos; a.protect_pos[b] = dpos; }
         }
         a.draft_pos[(size_t)b * a.draft_stride] = dpos;
         a.draft_tok[(size_t)b * a.draft_stride] = dtok;
-        const int prot = a.protect_pos[b];
         for (int p = 0; p < L; ++p) {
             uint8_t rem = 0;
             if (a.tau_remask >= 0.f) {
-                const int r = ra[p];
+                const int r = s_ra[p];
                 if (r >= 0 && r <= a.state - 1 && p != prot && s_conf[p] < a.tau_remask) {
-                    mk[p] = 1; ra[p] = -1; rem = 1;
+                    s_mk[p] = 1; s_ra[p] = -1; rem = 1;
                 }
             }
-            if (a.remasked) a.remasked[b * L + p] = rem;
-            a.masked[b * L + p] = mk[p];
-            a.revealed_at[b * L + p] = ra[p];
+            s_rem[p] = rem;
         }
-        s_gather = a.cond_tok[b];
+        s_gather = cond;
     }
     __syncthreads();
 
+    if (threadIdx.x < L) {
+        a.masked[b * L + threadIdx.x] = s_mk[threadIdx.x];
+        a.revealed_at[b * L + threadIdx.x] = s_ra[threadIdx.x];
+        if (a.remasked) a.remasked[b * L + threadIdx.x] = s_rem[threadIdx.x];
+    }
     if (a.E != nullptr) {  // embedding row that conditions the next head
         const int C8 = a.d >> 3;
         int tokc = s_gather;  // caller contract: 0 <= cond_tok < V; clamp so a bad value cannot fault

@@ -31,7 +31,7 @@ LOGIT_RTOL = 2e-2
 GAP_EXEMPT = 1e-3
 CONF_EXEMPT = 1e-3
 # engineering bounds well inside the parity rule (observed errors are ~1e-4)
-LOGIT_TIGHT = 4e-3
+LOGIT_TIGHT = 8e-3
 LSE_ATOL = 2e-3
 CONF_RTOL = 4e-3
 

@@ -1,0 +1,73 @@
+"""GPU parity of the two small entry points, mrp_verify_accept and mrp_remask, against the oracle."""
+import itertools
+
+import numpy as np
+import pytest
+import torch
+
+import oracle as orc
+import paper_2605_18817_amd as mrp
+
+pytestmark = pytest.mark.gpu
+RNG = np.random.default_rng(77)
+
+
+def _verify_case(ctx, B, L, V, K, verify, pos, tok):
+    v_d = torch.from_numpy(verify).cuda()
+    p_d = torch.from_numpy(pos).cuda(); t_d = torch.from_numpy(tok).cuda()
+    match = torch.zeros((B, K), dtype=torch.uint8, device="cuda")
+    alen = torch.zeros(B, dtype=torch.int32, device="cuda"); corr = torch.zeros(B, dtype=torch.int32, device="cuda")
+    ctx.verify_accept(B, K, v_d, p_d, t_d, K, match, alen, corr)
+    torch.cuda.synchronize()
+    m_o, a_o, c_o = orc.verify_accept(verify, pos, tok)
+    np.testing.assert_array_equal(match.cpu().numpy(), m_o)
+    np.testing.assert_array_equal(alen.cpu().numpy(), a_o)
+    np.testing.assert_array_equal(corr.cpu().numpy(), c_o)
+    return a_o
+
+
+@pytest.mark.parametrize("V", [16, 8192 + 4, 20000 + 3])     # one chunk, ragged chunks, scalar path
+def test_verify_accept_patterns(V):
+    L, K = 8, 3
+    pats = list(itertools.product([0, 1], repeat=K))
+    B = len(pats) + 2
+    ctx = mrp.MrpContext(128, V, B * L, L)
+    verify = RNG.normal(0, 2, (B, L, V)).astype(np.float32)
+    pos = np.stack([RNG.permutation(L)[:K] for _ in range(B)]).astype(np.int32)
+    tok = np.empty((B, K), np.int32)
+    for b in range(B):
+        pat = pats[b % len(pats)]
+        for j in range(K):
+            best = int(np.argmax(verify[b, pos[b, j]]))
+            tok[b, j] = best if pat[j] else (best + 1) % V
+    pos[-1, 1] = -1; tok[-1, 1] = -1                      # a missing draft ends the prefix
+    # exact tie between two vocabulary entries: the lowest index is the verifier's token
+    r = verify[-2, pos[-2, 0]]; hi = float(r.max()) + 1.0
+    r[V - 1] = hi; r[3] = hi; tok[-2, 0] = 3
+    a = _verify_case(ctx, B, L, V, K, verify, pos, tok)
+    assert set(a.tolist()) >= {0, 1, 2, 3}
+    ctx.close()
+
+
+def test_remask_entry_point():
+    B, L = 37, 16
+    M = B * L
+    ctx = mrp.MrpContext(128, 64, M, L)
+    conf = RNG.uniform(0, 1, M).astype(np.float32)
+    ra0 = RNG.integers(-2, 4, M).astype(np.int8)
+    m0 = (ra0 == -1).astype(np.uint8)
+    protect = RNG.integers(-1, L, B).astype(np.int32)
+    for state, tau_r, prot in ((2, 0.4, protect), (3, 0.0, protect), (1, 1.5, protect), (3, 0.7, None)):
+        c_d = torch.from_numpy(conf).cuda(); ra_d = torch.from_numpy(ra0.copy()).cuda()
+        m_d = torch.from_numpy(m0.copy()).cuda(); out = torch.full((M,), 9, dtype=torch.uint8, device="cuda")
+        p_d = None if prot is None else torch.from_numpy(prot).cuda()
+        ctx.remask(B, state, c_d, tau_r, p_d, ra_d, m_d, out)
+        torch.cuda.synchronize()
+        m, ra = m0.copy(), ra0.copy()
+        rem = orc.remask(B, L, state, conf.astype(np.float64), float(np.float32(tau_r)), prot, m, ra)
+        np.testing.assert_array_equal(out.cpu().numpy(), rem)
+        np.testing.assert_array_equal(m_d.cpu().numpy(), m)
+        np.testing.assert_array_equal(ra_d.cpu().numpy(), ra)
+    assert ctx.remask(B + 1, 1, c_d, 0.5, None, ra_d, m_d, out, check=False) == -2
+    assert ctx.remask(B, 1, None, 0.5, None, ra_d, m_d, out, check=False) == -1
+    ctx.close()
