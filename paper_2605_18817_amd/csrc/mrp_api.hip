@@ -20,6 +20,7 @@ struct mrp_ctx {
     int nT_max;         // partial tiles per row
     size_t part_rows;   // capacity of the k-split partial buffer, in rows of d floats
     int maxB;
+    bool use_tiled;     // 256 x 256 tiled GEMMs for M >= 768 (tuning switch, env MRP_TILED=0 disables)
     bool lm_persist;    // use the persistent LM-head kernel for M <= 128 (tuning switch, env MRP_LM_PERSIST)
     int nCU;            // compute units of the device (workgroups of the persistent LM-head kernel)
     char *ws;
@@ -135,6 +136,8 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     {   // tuning switch: MRP_LM_PERSIST=0 routes M <= 128 through the generic stream GEMM
         const char *e = getenv("MRP_LM_PERSIST");
         c->lm_persist = !(e && e[0] == '0');
+        const char *t = getenv("MRP_TILED");
+        c->use_tiled = !(t && t[0] == '0');
     }
     if (hipGetDevice(&c->device) != hipSuccess ||
         hipDeviceGetAttribute(&c->nCU, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->nCU < 1) {
@@ -276,30 +279,60 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
     for (int k = 1; k <= K; ++k) {
         const mrp_head &hd = heads[k - 1];
         StreamGemmArgs g;
+        // 256 x 256 tiles pay off once there are enough of them to fill the chip more than once
+        const bool tiled = c->use_tiled && M >= 768;
+        int nks1 = 1, nks2 = 1;
         // a = W1 [h_run ; e]
-        memset(&g, 0, sizeof(g));
-        g.Wp = static_cast<const uint4 *>(hd.W1_packed);
-        g.KBw = 2 * d / 16; g.n_rb = d / 32; g.nIb = c->nIb; g.M = M; g.R = d;
-        g.seg[0] = ActSeg{c->XH, c->plane, nkr_d, np_h};
-        g.seg[1] = ActSeg{c->XE, 0, nkr_d, 1};
-        g.nseg = 2;
-        g.nVt = d / WG_ROWS; g.nMg = nMg; g.G = 2 * nkr_d;
-        g.nKs = pick_ksplit(g.nVt, nMg, g.G, c->part_rows, M);
-        g.out = c->PART;
-        HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
-        HIP_TRY(c, launch_silu_split(c->PART, g.nKs, c->S, c->plane, c->nIb, M, d, st));
+        if (tiled) {
+            TiledGemmArgs tg;
+            memset(&tg, 0, sizeof(tg));
+            tg.Wp = static_cast<const uint4 *>(hd.W1_packed);
+            tg.KBw = 2 * d / 16; tg.n_rb = d / 32; tg.nIb = c->nIb; tg.M = M; tg.R = d;
+            tg.seg[0] = TiledSeg{c->XH, c->plane, d / 64, np_h};
+            tg.seg[1] = TiledSeg{c->XE, 0, d / 64, 1};
+            tg.nseg = 2;
+            tg.nMt = (M + 255) / 256; tg.nVt = (d + 255) / 256;
+            tg.out = c->PART;
+            HIP_TRY(c, launch_tiled_gemm(tg, EPI_PARTIAL, st));
+        } else {
+            memset(&g, 0, sizeof(g));
+            g.Wp = static_cast<const uint4 *>(hd.W1_packed);
+            g.KBw = 2 * d / 16; g.n_rb = d / 32; g.nIb = c->nIb; g.M = M; g.R = d;
+            g.seg[0] = ActSeg{c->XH, c->plane, nkr_d, np_h};
+            g.seg[1] = ActSeg{c->XE, 0, nkr_d, 1};
+            g.nseg = 2;
+            g.nVt = d / WG_ROWS; g.nMg = nMg; g.G = 2 * nkr_d;
+            g.nKs = pick_ksplit(g.nVt, nMg, g.G, c->part_rows, M);
+            g.out = c->PART;
+            nks1 = g.nKs;
+            HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
+        }
+        HIP_TRY(c, launch_silu_split(c->PART, nks1, c->S, c->plane, c->nIb, M, d, st));
         // u = W2 s
-        memset(&g, 0, sizeof(g));
-        g.Wp = static_cast<const uint4 *>(hd.W2_packed);
-        g.KBw = d / 16; g.n_rb = d / 32; g.nIb = c->nIb; g.M = M; g.R = d;
-        g.seg[0] = ActSeg{c->S, c->plane, nkr_d, NSPLIT};
-        g.nseg = 1;
-        g.nVt = d / WG_ROWS; g.nMg = nMg; g.G = nkr_d;
-        g.nKs = pick_ksplit(g.nVt, nMg, g.G, c->part_rows, M);
-        g.out = c->PART;
-        HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
+        if (tiled) {
+            TiledGemmArgs tg;
+            memset(&tg, 0, sizeof(tg));
+            tg.Wp = static_cast<const uint4 *>(hd.W2_packed);
+            tg.KBw = d / 16; tg.n_rb = d / 32; tg.nIb = c->nIb; tg.M = M; tg.R = d;
+            tg.seg[0] = TiledSeg{c->S, c->plane, d / 64, NSPLIT};
+            tg.nseg = 1;
+            tg.nMt = (M + 255) / 256; tg.nVt = (d + 255) / 256;
+            tg.out = c->PART;
+            HIP_TRY(c, launch_tiled_gemm(tg, EPI_PARTIAL, st));
+        } else {
+            memset(&g, 0, sizeof(g));
+            g.Wp = static_cast<const uint4 *>(hd.W2_packed);
+            g.KBw = d / 16; g.n_rb = d / 32; g.nIb = c->nIb; g.M = M; g.R = d;
+            g.seg[0] = ActSeg{c->S, c->plane, nkr_d, NSPLIT};
+            g.nseg = 1;
+            g.nVt = d / WG_ROWS; g.nMg = nMg; g.G = nkr_d;
+            g.nKs = pick_ksplit(g.nVt, nMg, g.G, c->part_rows, M);
+            g.out = c->PART;
+            nks2 = g.nKs;
+            HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
+        }
         // h_run += u ; y = bf16(RMSNorm(u) * gamma)
-        HIP_TRY(c, launch_norm(c->PART, g.nKs, static_cast<const uint16_t *>(hd.gamma), c->dims.rms_eps, h_run,
+        HIP_TRY(c, launch_norm(c->PART, nks2, static_cast<const uint16_t *>(hd.gamma), c->dims.rms_eps, h_run,
                                cfg->carry_hidden != 0, c->Y, c->XH, c->plane, c->nIb, M, d, st));
         if (cfg->carry_hidden) np_h = NSPLIT;
         // z += W_lm y, fused with the split-vocabulary (max, sum-exp, argmax) partials
@@ -317,6 +350,17 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
             la.z = z; la.pm = c->pm; la.ps = c->ps; la.pi = c->pi;
             HIP_TRY(c, launch_lm_persist(la, st));
             nT_lm = la.nWG * la.Pmax;
+        } else if (tiled && V % 4 == 0) {
+            TiledGemmArgs tg;
+            memset(&tg, 0, sizeof(tg));
+            tg.Wp = static_cast<const uint4 *>(W_lm_packed);
+            tg.KBw = d / 16; tg.n_rb = (V + 31) / 32; tg.nIb = c->nIb; tg.M = M; tg.R = V;
+            tg.seg[0] = TiledSeg{c->Y, 0, d / 64, 1};
+            tg.nseg = 1;
+            tg.nMt = (M + 255) / 256; tg.nVt = (V + 255) / 256;
+            tg.z = z; tg.pm = c->pm; tg.ps = c->ps; tg.pi = c->pi;
+            HIP_TRY(c, launch_tiled_gemm(tg, EPI_LM, st));
+            nT_lm = tg.nVt;
         } else {
             memset(&g, 0, sizeof(g));
             g.Wp = static_cast<const uint4 *>(W_lm_packed);

@@ -62,6 +62,25 @@ struct LmPersistArgs {
     int *pi;
 };
 
+// LDS-tiled GEMM (256 x 256 tiles) for many activation rows
+struct TiledSeg {
+    const uint4 *base;   // activation planes of this K segment
+    long plane_stride;
+    int nkq;             // k steps of 64 in this segment
+    int nplanes;
+};
+struct TiledGemmArgs {
+    const uint4 *Wp;
+    int KBw, n_rb, nIb, M, R;
+    TiledSeg seg[2];
+    int nseg;
+    int nMt, nVt;        // tiles along activation rows / weight rows
+    float *out;          // EPI_PARTIAL: [M][R]
+    float *z;            // EPI_LM: [M][R] in/out, partials [nVt][M]
+    float *pm, *ps;
+    int *pi;
+};
+
 // row-reduction partial: running max, sum of exp(x - max), index of the max
 struct Part {
     float m, s;
@@ -107,6 +126,7 @@ hipError_t launch_stream_gemm(const StreamGemmArgs &a, int epi, hipStream_t st);
 size_t stream_gemm_lds_bytes(int it);
 int stream_gemm_it(int M);   // activation row blocks per workgroup for M rows
 
+hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st);
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st);
 size_t lm_persist_lds_bytes();
 int lm_persist_pmax(int n_rb, int nWG);

@@ -77,6 +77,18 @@ def test_many_rows_wide_tile_static_top2():
     assert np.all((g.masked.reshape(cfg.B, cfg.L) == 0).sum(1) == 2 * (cfg.K + 1))
 
 
+def test_tiled_path_ragged_tiles():
+    # M = 800 >= 768 selects the 256 x 256 tiled kernels: 4 row tiles (the last with 32 rows),
+    # V = 1000 -> 4 vocabulary tiles (the last with 232 entries, 8 of them in a partial 32-block)
+    cfg = mi.straddling(mi.config(0, d=128, V=1000, B=50, L=16))
+    prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=0.5, tau_remask=0.3))
+    prob.close()
+    # same row count with a vocabulary that is not a multiple of 4: tiled head GEMMs, scalar LM-head path
+    cfg = mi.straddling(mi.config(0, d=256, V=1030, B=48, L=16, K=2))
+    prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=0.5))
+    prob.close()
+
+
 def test_weight_shared_heads_and_alg4_mode():
     # one module applied K times; reveal only at state 0, remask with the same tau (Algorithm 4)
     cfg = mi.straddling(mi.config(0, d=256, V=4096, B=8, L=8, K=2))
