@@ -131,7 +131,8 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS}
     roof["traffic"] = traffic_from_profile(cfg.cid)
-    roof["kernel"] = "stream_gemm (LM-head epilogue)"
+    roof["kernel"] = ("lm_persist_kernel" if M <= 128 and V % 4 == 0 else
+                      "tiled_gemm_kernel<EPI_LM>" if M >= 768 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
     roof["kernel_ms"] = lm_avg_ms
     roof["launches"] = len(lm_ms)
     roof["lm_head_share_of_step"] = (lm_avg_ms * K) / ms_per_step
@@ -140,7 +141,7 @@ def main() -> int:
     cpu = None
     if not args.skip_cpu_baseline:
         import oracle as orc
-        ns = min(B, max(1, int(os.environ.get("MRP_BENCH_ORACLE_SEQS", "8" if d <= 2048 else "1"))))
+        ns = min(B, max(1, int(os.environ.get("MRP_BENCH_ORACLE_SEQS", "16" if d <= 2048 else "2"))))
         seqs = list(range(ns))
         rows = np.concatenate([np.arange(b * L, (b + 1) * L) for b in seqs])
         oc = orc.make_cfg(d, V, ns, L, K, tau=cfg.tau, tau_remask=cfg.tau_remask)

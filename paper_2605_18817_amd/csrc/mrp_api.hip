@@ -67,7 +67,7 @@ Layout make_layout(const mrp_dims *dm, int nCU) {
     l.nT_max = nT_lm > nT_0 ? nT_lm : nT_0;
     const int nT_p = nCU * lm_persist_pmax((dm->V + 31) / 32, nCU);
     if (nT_p > l.nT_max) l.nT_max = nT_p;
-    l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 8 : (dm->max_rows < 1024 ? 1024 : dm->max_rows);
+    l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 16 : (dm->max_rows < 2048 ? 2048 : dm->max_rows);
     l.maxB = dm->max_rows / dm->block_len;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
@@ -107,7 +107,7 @@ bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 // k splits for a partial-sum GEMM so that small row counts still fill the chip
 int pick_ksplit(int nVt, int nMg, int G, size_t part_rows, int M) {
     int want = (512 + nVt * nMg - 1) / (nVt * nMg);
-    if (want > 8) want = 8;
+    if (want > 16) want = 16;
     if (want > G / 2) want = G / 2;
     if ((size_t)want * M > part_rows) want = (int)(part_rows / M);
     return want < 1 ? 1 : want;

@@ -90,6 +90,8 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *__restric
     }
 }
 
+constexpr int MERGE_BATCH = 16;  // strides of 64 partial tiles fetched together (1024 tiles per round trip)
+
 __device__ __forceinline__ bool more_confident(const float *conf, int a, int b) {
     if (conf[a] != conf[b]) return conf[a] > conf[b];
     return a < b;
@@ -119,11 +121,11 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
     for (int p = wave; p < L; p += 4) {
         const int i = b * L + p;
         Part pt = part_identity();
-        for (int t0 = 0; t0 < a.nT; t0 += 64 * 4) {
-            float m[4], sx[4];
-            int ix[4];
+        for (int t0 = 0; t0 < a.nT; t0 += 64 * MERGE_BATCH) {
+            float m[MERGE_BATCH], sx[MERGE_BATCH];
+            int ix[MERGE_BATCH];
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {  // issue the loads of four strides before merging any
+            for (int u = 0; u < MERGE_BATCH; ++u) {  // issue every load of the batch before merging any
                 const int t = t0 + u * 64 + lane;
                 const bool ok = t < a.nT;
                 const size_t o = (size_t)(ok ? t : 0) * a.M + i;
@@ -132,7 +134,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
                 ix[u] = ok ? a.pi[o] : 0x7fffffff;
             }
 #pragma unroll
-            for (int u = 0; u < 4; ++u) pt = part_merge(pt, Part{m[u], sx[u], ix[u]});
+            for (int u = 0; u < MERGE_BATCH; ++u) pt = part_merge(pt, Part{m[u], sx[u], ix[u]});
         }
         pt = wave_merge(pt);
         if (lane == 0) {
