@@ -155,7 +155,7 @@ def main() -> int:
                          f"{c1 - c0:.1f} s wall, fp64, gcc -O2 -fopenmp"}
 
     out = {
-        "metric": "MRP draft tokens/sec per step (B*block*K)",
+        "metric": "MRP draft tokens/sec per step (B\u00d7block\u00d7K) on 1 GPU; % HBM/MFMA roofline",
         "value": tokens_per_s,
         "unit": "tokens/s",
         "n_gpus": 1,
