@@ -89,6 +89,34 @@ __global__ __launch_bounds__(256) void gather_e_kernel(const uint16_t *__restric
     }
 }
 
+// Sum over the k-split partial buffers of the 8 floats at `off` (same order for any batching:
+// ((p0 + p1) + p2) + ...).  Four splits are fetched at a time so their latencies overlap.
+__device__ __forceinline__ void sum_partials(const float *__restrict__ part, size_t split_stride, int nKs, size_t off,
+                                             float (&x)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 0.f;
+    int ks = 0;
+    for (; ks + 4 <= nKs; ks += 4) {
+        float4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 *p = reinterpret_cast<const float4 *>(part + (size_t)(ks + u) * split_stride + off);
+            a[u] = p[0]; b[u] = p[1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            x[0] += a[u].x; x[1] += a[u].y; x[2] += a[u].z; x[3] += a[u].w;
+            x[4] += b[u].x; x[5] += b[u].y; x[6] += b[u].z; x[7] += b[u].w;
+        }
+    }
+    for (; ks < nKs; ++ks) {
+        const float4 *p = reinterpret_cast<const float4 *>(part + (size_t)ks * split_stride + off);
+        const float4 a = p[0], b = p[1];
+        x[0] += a.x; x[1] += a.y; x[2] += a.z; x[3] += a.w;
+        x[4] += b.x; x[5] += b.y; x[6] += b.z; x[7] += b.w;
+    }
+}
+
 __global__ __launch_bounds__(256) void silu_split_kernel(const float *__restrict__ part, int nKs,
                                                          uint4 *__restrict__ s_planes, long plane_stride, int nIb,
                                                          int M, int d) {
@@ -96,13 +124,8 @@ __global__ __launch_bounds__(256) void silu_split_kernel(const float *__restrict
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)M * C8) return;
     const int i = (int)(idx / C8), c8 = (int)(idx % C8);
-    float x[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int ks = 0; ks < nKs; ++ks) {
-        const float4 *p = reinterpret_cast<const float4 *>(part + ((size_t)ks * M + i) * d + 8 * c8);
-        const float4 a = p[0], b = p[1];
-        x[0] += a.x; x[1] += a.y; x[2] += a.z; x[3] += a.w;
-        x[4] += b.x; x[5] += b.y; x[6] += b.z; x[7] += b.w;
-    }
+    float x[8];
+    sum_partials(part, (size_t)M * d, nKs, (size_t)i * d + 8 * c8, x);
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = x[e] / (1.0f + expf(-x[e]));  // SiLU
     uint4 hi, mid, lo;
@@ -132,12 +155,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
 #pragma unroll
         for (int e = 0; e < 8; ++e) u[n][e] = 0.f;
         if (c8 < C8) {
-            for (int ks = 0; ks < nKs; ++ks) {
-                const float4 *p = reinterpret_cast<const float4 *>(part + ((size_t)ks * M + i) * d + 8 * c8);
-                const float4 a = p[0], b = p[1];
-                u[n][0] += a.x; u[n][1] += a.y; u[n][2] += a.z; u[n][3] += a.w;
-                u[n][4] += b.x; u[n][5] += b.y; u[n][6] += b.z; u[n][7] += b.w;
-            }
+            sum_partials(part, (size_t)M * d, nKs, (size_t)i * d + 8 * c8, u[n]);
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss += u[n][e] * u[n][e];
         }

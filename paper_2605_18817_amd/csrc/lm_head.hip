@@ -67,14 +67,16 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.Wp);
     const u32x4 *Yp = reinterpret_cast<const u32x4 *>(a.Y);
 
-    // unused partial slots of this workgroup hold the identity
-    if (tid < a.M) {
-        for (int p = P; p < a.Pmax; ++p) {
-            const size_t o = (size_t)(wg * a.Pmax + p) * a.M + tid;
-            a.pm[o] = -INFINITY; a.ps[o] = 0.f; a.pi[o] = 0x7fffffff;
+    // This workgroup's partial of every row: the passes' partials are merged in registers (thread i
+    // holds row i) and stored once, to slot wg of the row's contiguous slot array.
+    Part run_pt = part_identity();
+    if (P == 0) {
+        if (tid < a.M) {
+            const size_t o = (size_t)tid * a.nWG + wg;
+            a.pm[o] = run_pt.m; a.ps[o] = run_pt.s; a.pi[o] = run_pt.i;
         }
+        return;
     }
-    if (P == 0) return;
 
     // ---- weight prefetch cursor, flattened over passes.  Every load is unconditional: a wave
     // without a block in the cursor's pass re-reads block 0 (cache hits, no HBM traffic), so the
@@ -165,7 +167,7 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
             }
         }
     };
-    // after a barrier: merge the 8 waves' partials of pass p and store them
+    // after a barrier: merge the 8 waves' partials of pass p into the running partial
     auto write_partials = [&](int p) __attribute__((always_inline)) {
         const float *red_m = red_base + (p & 1) * RED_SET;
         const float *red_s = red_m + LM_WAVES * LM_ROWS;
@@ -175,10 +177,7 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
 #pragma unroll
             for (int wv = 1; wv < LM_WAVES; ++wv)
                 pt = part_merge(pt, Part{red_m[wv * LM_ROWS + tid], red_s[wv * LM_ROWS + tid], red_i[wv * LM_ROWS + tid]});
-            if (tid < a.M) {
-                const size_t o = (size_t)(wg * a.Pmax + p) * a.M + tid;
-                a.pm[o] = pt.m; a.ps[o] = pt.s; a.pi[o] = pt.i;
-            }
+            run_pt = part_merge(run_pt, pt);
         }
     };
 
@@ -250,6 +249,10 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         if constexpr (LM_RING >= 3) iter(std::integral_constant<int, 2>{});
         if constexpr (LM_RING >= 4) iter(std::integral_constant<int, 3>{});
     }
+    if (tid < a.M) {
+        const size_t o = (size_t)tid * a.nWG + wg;
+        a.pm[o] = run_pt.m; a.ps[o] = run_pt.s; a.pi[o] = run_pt.i;
+    }
 #undef LM_WLOAD
 #undef LM_YLOAD
 }
@@ -257,11 +260,6 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
 }  // namespace
 
 size_t lm_persist_lds_bytes() { return (size_t)2 * LM_STAGE * 16 + (size_t)2 * LM_WAVES * LM_ROWS * 12; }
-
-int lm_persist_pmax(int n_rb, int nWG) {
-    const int max_cnt = (n_rb + nWG - 1) / nWG;
-    return (max_cnt + LM_WAVES - 1) / LM_WAVES;
-}
 
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st) {
     static bool attr_set = false;

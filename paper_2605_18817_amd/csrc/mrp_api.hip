@@ -65,7 +65,7 @@ Layout make_layout(const mrp_dims *dm, int nCU) {
     const int nT_lm = ((dm->V + 31) / 32 + WG_WAVES - 1) / WG_WAVES;
     const int nT_0 = reduce_rows_tiles(dm->V);
     l.nT_max = nT_lm > nT_0 ? nT_lm : nT_0;
-    const int nT_p = nCU * lm_persist_pmax((dm->V + 31) / 32, nCU);
+    const int nT_p = nCU;  // persistent LM-head kernel: one slot per workgroup
     if (nT_p > l.nT_max) l.nT_max = nT_p;
     l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 16 : (dm->max_rows < 2048 ? 2048 : dm->max_rows);
     l.maxB = dm->max_rows / dm->block_len;
@@ -259,6 +259,7 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
         int nT0 = 0;
         HIP_TRY(c, launch_reduce_rows(z, M, V, c->pm, c->ps, c->pi, &nT0, st));
         sa.nT = nT0;
+        sa.slot_stride = 1; sa.row_stride = nT0;
         sa.state = off; sa.do_reveal = 1; sa.fresh = cfg->fresh_block; sa.write_protect = 1;
         sa.tau_remask = -1.f;
         sa.tok = io->tok; sa.conf = io->conf; sa.lse = io->lse;
@@ -339,6 +340,7 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
         const bool prof = c->prof_on && c->ev_used < PROF_PAIRS;
         if (prof) HIP_TRY(c, hipEventRecord(c->ev[2 * c->ev_used], st));
         int nT_lm = 0;
+        bool lm_rowmajor = false;  // partial layout [M][nT] (persistent kernel) or [nT][M]
         if (c->lm_persist && M <= 128 && V % 4 == 0) {
             LmPersistArgs la;
             memset(&la, 0, sizeof(la));
@@ -346,10 +348,11 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
             la.Y = c->Y;
             la.KB = d / 16; la.n_rb = (V + 31) / 32; la.nIb = c->nIb;
             la.M = M; la.V = V;
-            la.nWG = c->nCU; la.Pmax = lm_persist_pmax(la.n_rb, la.nWG);
+            la.nWG = c->nCU;
             la.z = z; la.pm = c->pm; la.ps = c->ps; la.pi = c->pi;
             HIP_TRY(c, launch_lm_persist(la, st));
-            nT_lm = la.nWG * la.Pmax;
+            nT_lm = la.nWG;
+            lm_rowmajor = true;
         } else if (tiled && V % 4 == 0) {
             TiledGemmArgs tg;
             memset(&tg, 0, sizeof(tg));
@@ -378,6 +381,8 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
         }
         // merge partials, reveal / draft / remask, gather the next conditioning embedding
         sa.nT = nT_lm;
+        sa.slot_stride = lm_rowmajor ? 1 : M;
+        sa.row_stride = lm_rowmajor ? nT_lm : 1;
         sa.state = off + k; sa.do_reveal = cfg->head_reveal; sa.fresh = 0; sa.write_protect = 0;
         sa.tau_remask = cfg->tau_remask;
         sa.tok = io->tok + (size_t)k * M; sa.conf = io->conf + (size_t)k * M; sa.lse = io->lse + (size_t)k * M;

@@ -56,9 +56,9 @@ struct LmPersistArgs {
     const uint4 *Y;    // packed bf16 activation plane [KB][nIb][64]
     int KB, n_rb, nIb;
     int M, V;
-    int nWG, Pmax;     // workgroups (one per CU) and passes per workgroup
+    int nWG;           // workgroups (one per CU)
     float *z;          // [M][V] in/out
-    float *pm, *ps;    // partials [nWG * Pmax][M]
+    float *pm, *ps;    // partials [M][nWG]: one slot per workgroup, a row's slots contiguous
     int *pi;
 };
 
@@ -129,7 +129,6 @@ int stream_gemm_it(int M);   // activation row blocks per workgroup for M rows
 hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st);
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st);
 size_t lm_persist_lds_bytes();
-int lm_persist_pmax(int n_rb, int nWG);
 
 hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, hipStream_t st);
 hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb,
@@ -146,6 +145,7 @@ struct SelectArgs {
     const float *pm, *ps;
     const int *pi;
     int nT;                 // partial tiles per row
+    long slot_stride, row_stride;  // partial (t, i) lives at t * slot_stride + i * row_stride
     int M, B, L, d, V;
     int state;              // global state index recorded in revealed_at
     int do_reveal;          // apply the reveal rule at this state

@@ -84,9 +84,11 @@ __global__ __launch_bounds__(256) void reduce_rows_kernel(const float *__restric
     p.s = s;
     p = block_merge(p, sm, ss, si);
     if (threadIdx.x == 0) {
-        pm[(size_t)t * M + i] = p.m;
-        ps[(size_t)t * M + i] = p.s;
-        pi[(size_t)t * M + i] = p.i;
+        // a row's partials are contiguous, so that the merge reads them coalesced
+        const size_t o = (size_t)i * gridDim.x + t;
+        pm[o] = p.m;
+        ps[o] = p.s;
+        pi[o] = p.i;
     }
 }
 
@@ -128,7 +130,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
             for (int u = 0; u < MERGE_BATCH; ++u) {  // issue every load of the batch before merging any
                 const int t = t0 + u * 64 + lane;
                 const bool ok = t < a.nT;
-                const size_t o = (size_t)(ok ? t : 0) * a.M + i;
+                const size_t o = (size_t)(ok ? t : 0) * a.slot_stride + (size_t)i * a.row_stride;
                 m[u] = ok ? a.pm[o] : -INFINITY;
                 sx[u] = ok ? a.ps[o] : 0.f;
                 ix[u] = ok ? a.pi[o] : 0x7fffffff;
