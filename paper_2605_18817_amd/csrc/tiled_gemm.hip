@@ -35,12 +35,25 @@ __device__ __forceinline__ bf16x8 as_frag(const u32x4 &u) { return __builtin_bit
 constexpr int TG_KB = 4;                    // 16-wide k blocks per step (64 k)
 constexpr int TG_B = TG_KB * 8 * 64;        // u32x4 of an activation stage (256 rows x 64 k)
 constexpr int TG_STAGE = TG_B;              // 32 KiB
-constexpr int TG_NLD = TG_B / 256;          // u32x4 per thread per step (8)
+constexpr int TG_NLD = TG_B / 256;          // 1 KiB chunks per wave per step (8)
+constexpr int TG_DEPTH = 3;                 // operand sets: steps s, s + 1, s + 2
+
+// One array per activation stage: the stage arrives by LDS-direct loads, and with separate
+// arrays the compiler's wait before reading one stage does not cover the loads into the others.
+__shared__ u32x4 tg_stage0[TG_STAGE];
+__shared__ u32x4 tg_stage1[TG_STAGE];
+__shared__ u32x4 tg_stage2[TG_STAGE];
+
+typedef const __attribute__((address_space(1))) void *gas_ptr;
+typedef __attribute__((address_space(3))) void *las_ptr;
+
+// Workgroup barrier after this wave's LDS accesses have completed; no fence, so the loads in
+// flight for later steps are not drained.
+__device__ __forceinline__ void tg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int EPI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void tiled_gemm_kernel(
     const TiledGemmArgs a) {
-    extern __shared__ u32x4 smem[];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wv = wave >> 1, wi = wave & 1;   // weight-row half, activation-row half
@@ -69,41 +82,60 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // k-step sequence: segments x (k quads) x planes
     const int seg0_steps = a.seg[0].nkq * a.seg[0].nplanes;
     const int nsteps = seg0_steps + (a.nseg > 1 ? a.seg[1].nkq * a.seg[1].nplanes : 0);
-    auto step_src = [&](int st, int &kbw, const u32x4 *&bptr) {
-        const bool s1 = st >= seg0_steps;
-        const int l = s1 ? st - seg0_steps : st;
-        const int np = s1 ? a.seg[1].nplanes : a.seg[0].nplanes;
-        const int kq = l / np, p = l - kq * np;
-        const int kq0 = s1 ? a.seg[0].nkq : 0;
-        kbw = (kq0 + kq) * TG_KB;
-        const uint4 *base = s1 ? a.seg[1].base : a.seg[0].base;
-        const long pstr = s1 ? a.seg[1].plane_stride : a.seg[0].plane_stride;
-        bptr = reinterpret_cast<const u32x4 *>(base) + (size_t)p * pstr + ((size_t)(kq * TG_KB) * a.nIb + ib0) * 64;
+    // Cursor over the k steps (segment, k quad, plane), advanced one step at a time without
+    // divisions; it stops on the last step, which the padded tail re-fetches.  The segment
+    // descriptions are copied out of the kernel arguments once (and made opaque, so that they
+    // are not re-read from memory in every step).
+    long seg_base0 = (long)a.seg[0].base, seg_base1 = (long)a.seg[1].base;
+    long seg_ps0 = a.seg[0].plane_stride, seg_ps1 = a.seg[1].plane_stride;
+    int seg_np0 = a.seg[0].nplanes, seg_np1 = a.seg[1].nplanes;
+    int seg_nkq0 = a.seg[0].nkq;
+    asm volatile("" : "+s"(seg_base0), "+s"(seg_base1), "+s"(seg_ps0), "+s"(seg_ps1), "+s"(seg_np0), "+s"(seg_np1),
+                 "+s"(seg_nkq0));
+    const long kq_stride = (long)TG_KB * a.nIb * 64;   // u32x4 per k quad of a plane
+    int cu_st = 0, cu_seg = 0, cu_kq = 0, cu_p = 0;
+    auto cursor_get = [&](int &kbw, const u32x4 *&bptr) __attribute__((always_inline)) {
+        kbw = ((cu_seg ? seg_nkq0 : 0) + cu_kq) * TG_KB;
+        const long base = cu_seg ? seg_base1 : seg_base0;
+        const long ps = cu_seg ? seg_ps1 : seg_ps0;
+        bptr = reinterpret_cast<const u32x4 *>(base) + (cu_p * ps + cu_kq * kq_stride + (long)ib0 * 64);
+    };
+    auto cursor_next = [&]() __attribute__((always_inline)) {
+        if (cu_st + 1 < nsteps) {
+            ++cu_st;
+            if (++cu_p == (cu_seg ? seg_np1 : seg_np0)) {
+                cu_p = 0;
+                if (++cu_kq == seg_nkq0 && cu_seg == 0) { cu_kq = 0; cu_seg = 1; }
+            }
+        }
     };
 
-    // Operands of the next step are fetched while this one computes: first the activation
-    // chunk (to staging registers, then LDS), then the weight fragments (kept in registers),
-    // so that waiting for the older activation loads leaves the weight loads in flight.
-    u32x4 areg[2][4][TG_KB];   // [step parity][row block][k block]
-    u32x4 bst[TG_NLD];
-#define TG_LOAD(st, set)                                                                   \
+    // Operands are requested two steps ahead.  Per step and wave: 8 LDS-direct loads (this wave's
+    // quarter of the 32 KiB activation stage) and then 16 weight-fragment loads into the
+    // register set of that step; requests complete in issue order.
+    u32x4 areg[TG_DEPTH][4][TG_KB];   // [step % 3][row block][k block]
+#define TG_LOAD(st, set, stage)                                                            \
     {                                                                                      \
         int kbw_;                                                                          \
         const u32x4 *bp_;                                                                  \
-        step_src((st) < nsteps ? (st) : nsteps - 1, kbw_, bp_);                            \
-        _Pragma("unroll") for (int n = 0; n < TG_NLD; ++n)                                 \
-            bst[n] = bp_[(size_t)(n >> 1) * a.nIb * 64 + tid + 256 * (n & 1)];              \
+        cursor_get(kbw_, bp_);                                                             \
+        cursor_next();                                                                     \
+        _Pragma("unroll") for (int n = 0; n < TG_NLD; ++n) {                               \
+            const int c = wave + 4 * n;            /* chunk: k block c / 8, row block c % 8 */ \
+            __builtin_amdgcn_global_load_lds(                                              \
+                (gas_ptr)(bp_ + ((size_t)(c >> 3) * a.nIb + (c & 7)) * 64 + lane),         \
+                (las_ptr)((stage) + c * 64), 16, 0, 0);                                    \
+        }                                                                                  \
+        __builtin_amdgcn_sched_barrier(0);                                                 \
         _Pragma("unroll") for (int v4 = 0; v4 < 4; ++v4)                                   \
             _Pragma("unroll") for (int kb = 0; kb < TG_KB; ++kb)                           \
                 areg[set][v4][kb] = asrc[v4][(size_t)(kbw_ + kb) * 64];                    \
     }
-#define TG_STORE(buf)                                                                      \
-    {                                                                                      \
-        u32x4 *db_ = smem + (buf) * TG_STAGE;                                              \
-        _Pragma("unroll") for (int n = 0; n < TG_NLD; ++n) db_[tid + 256 * n] = bst[n];    \
-    }
+    // the group requested one step ago is complete when at most the youngest group (24) is pending
+#define TG_WAIT_PREV() __builtin_amdgcn_s_waitcnt(0x4F78)   /* vmcnt(24) */
 
-    TG_LOAD(0, 0)
+    TG_LOAD(0, 0, tg_stage0)
+    TG_LOAD(1, 1, tg_stage1)
 
     f32x16 acc[4][4];
 #pragma unroll
@@ -112,47 +144,87 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         for (int it = 0; it < 4; ++it)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[v4][it][r] = 0.f;
-    TG_STORE(0)
-    __syncthreads();
+    TG_WAIT_PREV();
+    tg_barrier();
 
     // activation fragments are double-buffered: the LDS reads of the next k block are issued
     // before the MFMAs of the current one (one wave per SIMD: nothing else hides them)
     bf16x8 bf[2][4];
-#define TG_FRAGS(buf, kb, set)                                                             \
-    {                                                                                      \
-        const u32x4 *B_ = smem + (buf) * TG_STAGE;                                         \
-        _Pragma("unroll") for (int it = 0; it < 4; ++it)                                   \
-            bf[set][it] = as_frag(B_[((kb) * 8 + wi * 4 + it) * 64 + lane]);               \
-    }
+#define TG_FRAGS(stage, kb, set)                                                           \
+    _Pragma("unroll") for (int it = 0; it < 4; ++it)                                       \
+        bf[set][it] = as_frag((stage)[((kb) * 8 + wi * 4 + it) * 64 + lane]);
 #define TG_MFMA(par, kb, set)                                                              \
     _Pragma("unroll") for (int v4 = 0; v4 < 4; ++v4)                                       \
         _Pragma("unroll") for (int it = 0; it < 4; ++it)                                   \
             acc[v4][it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(areg[par][v4][kb]), bf[set][it], acc[v4][it], 0, 0, 0);
 
-    TG_FRAGS(0, 0, 0)
-    auto step = [&](auto par_c, int st) __attribute__((always_inline)) {
-        constexpr int PAR = decltype(par_c)::value;   // st & 1: LDS buffer and weight register set
-        TG_LOAD(st + 1, PAR ^ 1)                       // (past the end: re-fetches the last step, never used)
-        __builtin_amdgcn_sched_barrier(0);             // keep the fetches at the top of the step
-        TG_FRAGS(PAR, 1, 1)
-        TG_MFMA(PAR, 0, 0)
-        TG_FRAGS(PAR, 2, 0)
-        TG_MFMA(PAR, 1, 1)
-        TG_FRAGS(PAR, 3, 1)
-        TG_MFMA(PAR, 2, 0)
-        // every read of this step's buffer is done; hand over the next step's activations
-        TG_STORE(PAR ^ 1)
-        __syncthreads();
-        TG_FRAGS(PAR ^ 1, 0, 0)
-        TG_MFMA(PAR, 3, 1)
+    // One k step.  A wave issues in order, and a memory request that finds the request queue full
+    // holds up the MFMAs behind it, so the step's 24 requests are spread between its 64 MFMAs
+    // (one or two ahead of every group of four) instead of being issued in a burst.
+    int kbw_n;
+    const u32x4 *bp_n;
+    auto step = [&](auto par_c, auto guard_c, int st, const u32x4 *cur, u32x4 *after) __attribute__((always_inline)) {
+        constexpr int PAR = decltype(par_c)::value;   // st % 3: activation stage and weight register set
+        constexpr int NS = (PAR + 2) % TG_DEPTH;      // set and stage (`after`) of step st + 2
+        constexpr bool GUARD = decltype(guard_c)::value;
+        // (`after` was last read one step ago and every wave has passed the barrier since;
+        //  past the end the last step is re-fetched, never used)
+        const bool live = !GUARD || st < nsteps;
+        if (live) { TG_FRAGS(cur, 0, 0) }
+#pragma unroll
+        for (int kb = 0; kb < TG_KB; ++kb) {
+#pragma unroll
+            for (int v4 = 0; v4 < 4; ++v4) {
+                const int c = kb * 4 + v4;             // group 0..15: requests go ahead of groups 1..15
+                if (c >= 1) {
+                    const int wl = c - 1;              // weight fragment 0..14 (15 goes with group 15)
+                    areg[NS][wl >> 2][wl & 3] = asrc[wl >> 2][(size_t)(kbw_n + (wl & 3)) * 64];
+                    if (c == 15) areg[NS][3][3] = asrc[3][(size_t)(kbw_n + 3) * 64];
+                    if (c & 1) {
+                        const int ch = wave + 4 * (c >> 1);   // chunk: k block ch / 8, row block ch % 8
+                        __builtin_amdgcn_global_load_lds(
+                            (gas_ptr)(bp_n + ((size_t)(ch >> 3) * a.nIb + (ch & 7)) * 64 + lane),
+                            (las_ptr)(after + ch * 64), 16, 0, 0);
+                    }
+                }
+                if (live) {
+                    if (kb + 1 < TG_KB)
+                        bf[(kb + 1) & 1][v4] = as_frag(cur[((kb + 1) * 8 + wi * 4 + v4) * 64 + lane]);
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int it = 0; it < 4; ++it)
+                        acc[v4][it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(areg[PAR][v4][kb]), bf[kb & 1][it],
+                                                                              acc[v4][it], 0, 0, 0);
+                }
+                if (c == 0) {   // behind the first MFMAs: where step st + 2's operands are
+                    cursor_get(kbw_n, bp_n);
+                    cursor_next();
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        TG_WAIT_PREV();
+        tg_barrier();
     };
-    // (the step count is even: every segment has d / 64 k steps per plane and d % 128 == 0)
-    for (int st = 0; st < nsteps; st += 2) {
-        step(std::integral_constant<int, 0>{}, st);
-        step(std::integral_constant<int, 1>{}, st + 1);
+    {
+        using T = std::true_type;
+        using F = std::false_type;
+        int st = 0;
+        for (; st + TG_DEPTH <= nsteps; st += TG_DEPTH) {
+            step(std::integral_constant<int, 0>{}, F{}, st, tg_stage0, tg_stage2);
+            step(std::integral_constant<int, 1>{}, F{}, st + 1, tg_stage1, tg_stage0);
+            step(std::integral_constant<int, 2>{}, F{}, st + 2, tg_stage2, tg_stage1);
+        }
+        if (st < nsteps) {   // the last one or two steps
+            step(std::integral_constant<int, 0>{}, T{}, st, tg_stage0, tg_stage2);
+            step(std::integral_constant<int, 1>{}, T{}, st + 1, tg_stage1, tg_stage0);
+            step(std::integral_constant<int, 2>{}, T{}, st + 2, tg_stage2, tg_stage1);
+        }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the padded tail's LDS-direct loads have landed
+    tg_barrier();
 #undef TG_LOAD
-#undef TG_STORE
+#undef TG_WAIT_PREV
 #undef TG_FRAGS
 #undef TG_MFMA
 
@@ -178,12 +250,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             }
     } else {
         // per wave: 128 activation rows x 128 vocabulary entries.  The logit tile is added here,
-        // one 32-row slice (64 registers) at a time, the next slice's loads in flight meanwhile;
-        // the row reduction over v runs in registers.
-        float *red_m = reinterpret_cast<float *>(smem);            // [2 (wv)][256 rows] (LDS stages are dead)
+        // one 32-row slice (64 registers) at a time; the row reduction over v runs in registers.
+        float *red_m = reinterpret_cast<float *>(tg_stage0);       // [2 (wv)][256 rows] (the stages are dead)
         float *red_s = red_m + 512;
         int *red_i = reinterpret_cast<int *>(red_s + 512);
-        float4 zc[2][16];
+        // Three slices of the logit tile are requested up front and the fourth right after the first
+        // slice's stores: requests complete in issue order, so a load queued behind many stores
+        // would wait for all of them.  The sum is formed in place in the fetched registers.
+        float4 zc[3][16];
         auto zfetch = [&](int it, float4 (&dst)[16]) __attribute__((always_inline)) {
             const int i = (ib0 + wi * 4 + it) * 32 + lne;
 #pragma unroll
@@ -197,41 +271,40 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         };
         zfetch(0, zc[0]);
         zfetch(1, zc[1]);
+        zfetch(2, zc[2]);
 #pragma unroll
         for (int it = 0; it < 4; ++it) {
             const int i = (ib0 + wi * 4 + it) * 32 + lne;
+            float4(&xs)[16] = zc[it % 3];
             Part pt = part_identity();
-            float xs[4][16];
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int v = (rb0 + wv * 4 + v4) * 32 + 8 * q + 4 * lh;
-                    const float4 zz = zc[it & 1][v4 * 4 + q];
-                    xs[v4][4 * q + 0] = acc[v4][it][4 * q + 0] + zz.x;
-                    xs[v4][4 * q + 1] = acc[v4][it][4 * q + 1] + zz.y;
-                    xs[v4][4 * q + 2] = acc[v4][it][4 * q + 2] + zz.z;
-                    xs[v4][4 * q + 3] = acc[v4][it][4 * q + 3] + zz.w;
-                    if (i < a.M && v < a.R)
-                        *reinterpret_cast<float4 *>(a.z + (size_t)i * a.R + v) =
-                            make_float4(xs[v4][4 * q], xs[v4][4 * q + 1], xs[v4][4 * q + 2], xs[v4][4 * q + 3]);
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float xx = xs[v4][4 * q + e];
-                        if (v < a.R && xx > pt.m) { pt.m = xx; pt.i = v + e; }
+                    float4 &x4 = xs[v4 * 4 + q];
+                    x4.x += acc[v4][it][4 * q + 0];
+                    x4.y += acc[v4][it][4 * q + 1];
+                    x4.z += acc[v4][it][4 * q + 2];
+                    x4.w += acc[v4][it][4 * q + 3];
+                    if (i < a.M && v < a.R) *reinterpret_cast<float4 *>(a.z + (size_t)i * a.R + v) = x4;
+                    if (v < a.R) {
+                        if (x4.x > pt.m) { pt.m = x4.x; pt.i = v; }
+                        if (x4.y > pt.m) { pt.m = x4.y; pt.i = v + 1; }
+                        if (x4.z > pt.m) { pt.m = x4.z; pt.i = v + 2; }
+                        if (x4.w > pt.m) { pt.m = x4.w; pt.i = v + 3; }
                     }
                 }
-            if (it + 2 < 4) zfetch(it + 2, zc[it & 1]);
             float sum = 0.f;
 #pragma unroll
             for (int v4 = 0; v4 < 4; ++v4)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const bool ok = (rb0 + wv * 4 + v4) * 32 + 8 * q + 4 * lh < a.R;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        if (ok) sum += __expf(xs[v4][4 * q + e] - pt.m);
+                    const float4 x4 = xs[v4 * 4 + q];
+                    if (ok) sum += (__expf(x4.x - pt.m) + __expf(x4.y - pt.m)) + (__expf(x4.z - pt.m) + __expf(x4.w - pt.m));
                 }
+            if (it == 0) zfetch(3, zc[0]);   // (its registers are free again)
             pt.s = sum;
             Part other;
             other.m = __shfl_xor(pt.m, 32);
@@ -261,19 +334,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
 template <int EPI>
 hipError_t launch_inst(const TiledGemmArgs &a, hipStream_t st) {
-    static bool attr_set = false;
-    const size_t lds = (size_t)2 * TG_STAGE * 16;   // 64 KiB (the reduction scratch of EPI_LM reuses it)
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(tiled_gemm_kernel<EPI>),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int nMgrp = (a.nMt + 3) / 4, nVch = (a.nVt + 7) / 8;
     const int nsb = nMgrp * nVch;
     const int per_xcd = (nsb + 7) / 8;          // super-blocks per XCD
     const int grid = per_xcd * 32 * 8;
-    hipLaunchKernelGGL(tiled_gemm_kernel<EPI>, dim3(grid), dim3(256), lds, st, a);
+    hipLaunchKernelGGL(tiled_gemm_kernel<EPI>, dim3(grid), dim3(256), 0, st, a);
     return hipGetLastError();
 }
 
