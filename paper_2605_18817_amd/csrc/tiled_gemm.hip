@@ -1,17 +1,17 @@
 // Tiled bf16 MFMA GEMM for many activation rows (the MFMA-bound regime of the MRP
 // chain):  out[i][r] (+)= sum_k W[r][k] * X[i][k]  with 256 x 256 output tiles.
 //
-// A workgroup of four wavefronts (2 x 2) computes a tile of 256 weight rows x 256
-// activation rows; each wave owns 128 x 128 of it as 4 x 4 MFMA 32x32x16 tiles (256
-// fp32 accumulators).  The weight fragments go from the packed layout straight into
-// MFMA operand registers (one contiguous 1 KiB read per 32 rows x 16 k, fetched one k
-// step ahead); only the activation operand passes through LDS (double-buffered 32 KiB
-// stages, read back conflict-free one block per ds_read_b128).  Keeping the weights out
-// of LDS matters because LDS would otherwise be as busy as the matrix cores: at one
-// wave per SIMD, 64 KiB of ds_write_b128 (about 60 B/clk) plus 128 KiB of ds_read_b128
-// (128 B/clk) per k step take as long as the step's 64 MFMAs.  As in the streaming
-// kernels the weight fragment is the MFMA "A" operand, so a lane's accumulators of a
-// sub-tile are 16 outputs of one activation row.
+// A workgroup of four wavefronts computes a tile of 256 weight rows x 256 activation rows;
+// each wave owns 64 weight rows x all 256 activation rows as 2 x 8 MFMA 32x32x16 tiles (256
+// fp32 accumulators).  The weight fragments go from the packed layout straight into MFMA
+// operand registers (one contiguous 1 KiB read per 32 rows x 16 k); no two waves load the
+// same fragment.  The activation operand arrives in LDS by LDS-direct loads (three 32 KiB
+// stages) and every wave reads all of it.  What limits this kernel is how many memory
+// requests the CU's address unit takes per k step next to the MFMAs of four single-wave
+// SIMDs, so the layout is the one with the fewest request bytes (64 KiB per step), operands
+// are requested two steps ahead, and the requests are spread between the MFMAs.  As in the
+// streaming kernels the weight fragment is the MFMA "A" operand, so a lane's accumulators of
+// a sub-tile are 16 outputs of one activation row.
 //
 // Workgroups are ordered so that the 32 CUs of one XCD work at the same time on a
 // block of 4 (activation) x 8 (weight) tiles and share its operand slices in that
@@ -56,7 +56,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const TiledGemmArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wv = wave >> 1, wi = wave & 1;   // weight-row half, activation-row half
     const int ln = lane & 31, lh = lane >> 5;
 
     // ---- workgroup -> tile (XCD-aware) ----
@@ -70,13 +69,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int rb0 = vt * 8, ib0 = mt * 8;
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.Wp);
 
-    // this wave's four weight row blocks (rows past the padded matrix re-read the last block)
-    const u32x4 *asrc[4];
+    // this wave's two weight row blocks (rows past the padded matrix re-read the last block)
+    const u32x4 *asrc[2];
 #pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4) {
-        int rb = rb0 + wv * 4 + v4;
+    for (int v2 = 0; v2 < 2; ++v2) {
+        int rb = rb0 + wave * 2 + v2;
         rb = rb < a.n_rb ? rb : a.n_rb - 1;
-        asrc[v4] = Wp + (size_t)rb * a.KBw * 64 + lane;
+        asrc[v2] = Wp + (size_t)rb * a.KBw * 64 + lane;
     }
 
     // k-step sequence: segments x (k quads) x planes
@@ -111,9 +110,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     };
 
     // Operands are requested two steps ahead.  Per step and wave: 8 LDS-direct loads (this wave's
-    // quarter of the 32 KiB activation stage) and then 16 weight-fragment loads into the
-    // register set of that step; requests complete in issue order.
-    u32x4 areg[TG_DEPTH][4][TG_KB];   // [step % 3][row block][k block]
+    // quarter of the 32 KiB activation stage) and 8 weight-fragment loads into the register set
+    // of that step; requests complete in issue order.
+    u32x4 areg[TG_DEPTH][2][TG_KB];   // [step % 3][row block][k block]
 #define TG_LOAD(st, set, stage)                                                            \
     {                                                                                      \
         int kbw_;                                                                          \
@@ -127,40 +126,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 (las_ptr)((stage) + c * 64), 16, 0, 0);                                    \
         }                                                                                  \
         __builtin_amdgcn_sched_barrier(0);                                                 \
-        _Pragma("unroll") for (int v4 = 0; v4 < 4; ++v4)                                   \
+        _Pragma("unroll") for (int v2 = 0; v2 < 2; ++v2)                                   \
             _Pragma("unroll") for (int kb = 0; kb < TG_KB; ++kb)                           \
-                areg[set][v4][kb] = asrc[v4][(size_t)(kbw_ + kb) * 64];                    \
+                areg[set][v2][kb] = asrc[v2][(size_t)(kbw_ + kb) * 64];                    \
     }
-    // the group requested one step ago is complete when at most the youngest group (24) is pending
-#define TG_WAIT_PREV() __builtin_amdgcn_s_waitcnt(0x4F78)   /* vmcnt(24) */
+    // the group requested one step ago is complete when at most the youngest group (16) is pending
+#define TG_WAIT_PREV() __builtin_amdgcn_s_waitcnt(0x4F70)   /* vmcnt(16) */
 
     TG_LOAD(0, 0, tg_stage0)
     TG_LOAD(1, 1, tg_stage1)
 
-    f32x16 acc[4][4];
+    f32x16 acc[2][8];
 #pragma unroll
-    for (int v4 = 0; v4 < 4; ++v4)
+    for (int v2 = 0; v2 < 2; ++v2)
 #pragma unroll
-        for (int it = 0; it < 4; ++it)
+        for (int ib = 0; ib < 8; ++ib)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[v4][it][r] = 0.f;
+            for (int r = 0; r < 16; ++r) acc[v2][ib][r] = 0.f;
     TG_WAIT_PREV();
     tg_barrier();
 
     // activation fragments are double-buffered: the LDS reads of the next k block are issued
-    // before the MFMAs of the current one (one wave per SIMD: nothing else hides them)
-    bf16x8 bf[2][4];
-#define TG_FRAGS(stage, kb, set)                                                           \
-    _Pragma("unroll") for (int it = 0; it < 4; ++it)                                       \
-        bf[set][it] = as_frag((stage)[((kb) * 8 + wi * 4 + it) * 64 + lane]);
-#define TG_MFMA(par, kb, set)                                                              \
-    _Pragma("unroll") for (int v4 = 0; v4 < 4; ++v4)                                       \
-        _Pragma("unroll") for (int it = 0; it < 4; ++it)                                   \
-            acc[v4][it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(areg[par][v4][kb]), bf[set][it], acc[v4][it], 0, 0, 0);
+    // among the MFMAs of the current one (one wave per SIMD: nothing else hides them)
+    bf16x8 bf[2][8];
 
     // One k step.  A wave issues in order, and a memory request that finds the request queue full
-    // holds up the MFMAs behind it, so the step's 24 requests are spread between its 64 MFMAs
-    // (one or two ahead of every group of four) instead of being issued in a burst.
+    // holds up the MFMAs behind it, so the step's 16 requests are spread between its 64 MFMAs
+    // (one ahead of every group of four but the first) instead of being issued in a burst.
     int kbw_n;
     const u32x4 *bp_n;
     auto step = [&](auto par_c, auto guard_c, int st, const u32x4 *cur, u32x4 *after) __attribute__((always_inline)) {
@@ -170,31 +162,39 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         // (`after` was last read one step ago and every wave has passed the barrier since;
         //  past the end the last step is re-fetched, never used)
         const bool live = !GUARD || st < nsteps;
-        if (live) { TG_FRAGS(cur, 0, 0) }
+        if (live) {
+#pragma unroll
+            for (int ib = 0; ib < 8; ++ib) bf[0][ib] = as_frag(cur[ib * 64 + lane]);
+        }
 #pragma unroll
         for (int kb = 0; kb < TG_KB; ++kb) {
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4) {
-                const int c = kb * 4 + v4;             // group 0..15: requests go ahead of groups 1..15
-                if (c >= 1) {
-                    const int wl = c - 1;              // weight fragment 0..14 (15 goes with group 15)
-                    areg[NS][wl >> 2][wl & 3] = asrc[wl >> 2][(size_t)(kbw_n + (wl & 3)) * 64];
-                    if (c == 15) areg[NS][3][3] = asrc[3][(size_t)(kbw_n + 3) * 64];
-                    if (c & 1) {
-                        const int ch = wave + 4 * (c >> 1);   // chunk: k block ch / 8, row block ch % 8
+            for (int g4 = 0; g4 < 4; ++g4) {
+                const int c = kb * 4 + g4;             // group 0..15
+                if (c >= 1) {                          // requests 0..14 (15 goes with group 15, too)
+                    const int rq = c - 1;
+                    if (rq & 1) {
+                        const int wl = rq >> 1;        // weight fragment 0..6 (7 below)
+                        areg[NS][wl >> 2][wl & 3] = asrc[wl >> 2][(size_t)(kbw_n + (wl & 3)) * 64];
+                    } else {
+                        const int ch = wave + 4 * (rq >> 1);   // chunk: k block ch / 8, row block ch % 8
                         __builtin_amdgcn_global_load_lds(
                             (gas_ptr)(bp_n + ((size_t)(ch >> 3) * a.nIb + (ch & 7)) * 64 + lane),
                             (las_ptr)(after + ch * 64), 16, 0, 0);
                     }
+                    if (c == 15) areg[NS][1][3] = asrc[1][(size_t)(kbw_n + 3) * 64];
                 }
                 if (live) {
-                    if (kb + 1 < TG_KB)
-                        bf[(kb + 1) & 1][v4] = as_frag(cur[((kb + 1) * 8 + wi * 4 + v4) * 64 + lane]);
+                    if (kb + 1 < TG_KB) {
+                        bf[(kb + 1) & 1][2 * g4] = as_frag(cur[((kb + 1) * 8 + 2 * g4) * 64 + lane]);
+                        bf[(kb + 1) & 1][2 * g4 + 1] = as_frag(cur[((kb + 1) * 8 + 2 * g4 + 1) * 64 + lane]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
+                    const int v2 = g4 >> 1, i0 = (g4 & 1) * 4;
 #pragma unroll
                     for (int it = 0; it < 4; ++it)
-                        acc[v4][it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(areg[PAR][v4][kb]), bf[kb & 1][it],
-                                                                              acc[v4][it], 0, 0, 0);
+                        acc[v2][i0 + it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                            as_frag(areg[PAR][v2][kb]), bf[kb & 1][i0 + it], acc[v2][i0 + it], 0, 0, 0);
                 }
                 if (c == 0) {   // behind the first MFMAs: where step st + 2's operands are
                     cursor_get(kbw_n, bp_n);
@@ -225,8 +225,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     tg_barrier();
 #undef TG_LOAD
 #undef TG_WAIT_PREV
-#undef TG_FRAGS
-#undef TG_MFMA
 
     // ---- epilogue ----
     // (an opaque zero keeps the compiler from sharing the prologue's 64 tile addresses with
@@ -236,57 +234,57 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int lne = ln + opq;
     if constexpr (EPI == EPI_PARTIAL) {
 #pragma unroll
-        for (int v4 = 0; v4 < 4; ++v4)
+        for (int v2 = 0; v2 < 2; ++v2)
 #pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int i = (ib0 + wi * 4 + it) * 32 + lne;
+            for (int ib = 0; ib < 8; ++ib) {
+                const int i = (ib0 + ib) * 32 + lne;
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int r = (rb0 + wv * 4 + v4) * 32 + 8 * q + 4 * lh;
+                    const int r = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh;
                     if (i < a.M && r < a.R)
                         *reinterpret_cast<float4 *>(a.out + (size_t)i * a.R + r) = make_float4(
-                            acc[v4][it][4 * q], acc[v4][it][4 * q + 1], acc[v4][it][4 * q + 2], acc[v4][it][4 * q + 3]);
+                            acc[v2][ib][4 * q], acc[v2][ib][4 * q + 1], acc[v2][ib][4 * q + 2], acc[v2][ib][4 * q + 3]);
                 }
             }
     } else {
-        // per wave: 128 activation rows x 128 vocabulary entries.  The logit tile is added here,
-        // one 32-row slice (64 registers) at a time; the row reduction over v runs in registers.
-        float *red_m = reinterpret_cast<float *>(tg_stage0);       // [2 (wv)][256 rows] (the stages are dead)
-        float *red_s = red_m + 512;
-        int *red_i = reinterpret_cast<int *>(red_s + 512);
-        // Three slices of the logit tile are requested up front and the fourth right after the first
-        // slice's stores: requests complete in issue order, so a load queued behind many stores
-        // would wait for all of them.  The sum is formed in place in the fetched registers.
-        float4 zc[3][16];
-        auto zfetch = [&](int it, float4 (&dst)[16]) __attribute__((always_inline)) {
-            const int i = (ib0 + wi * 4 + it) * 32 + lne;
+        // per wave: 256 activation rows x 64 vocabulary entries.  The logit tile is added here, one
+        // 32-row slice (32 registers) at a time; the row reduction over v runs in registers.
+        float *red_m = reinterpret_cast<float *>(tg_stage0);       // [4 waves][256 rows] (the stages are dead)
+        float *red_s = red_m + 1024;
+        int *red_i = reinterpret_cast<int *>(red_s + 1024);
+        // Five slices of the logit tile are in flight ahead of the one being added; the sum is
+        // formed in place in the fetched registers.
+        constexpr int ZD = 6;
+        float4 zc[ZD][8];
+        auto zfetch = [&](int ib, float4 (&dst)[8]) __attribute__((always_inline)) {
+            const int i = (ib0 + ib) * 32 + lne;
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4)
+            for (int v2 = 0; v2 < 2; ++v2)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int v = (rb0 + wv * 4 + v4) * 32 + 8 * q + 4 * lh;
-                    dst[v4 * 4 + q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (i < a.M && v < a.R) dst[v4 * 4 + q] = *reinterpret_cast<const float4 *>(a.z + (size_t)i * a.R + v);
+                    const int v = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh;
+                    dst[v2 * 4 + q] = make_float4(0.f, 0.f, 0.f, 0.f);
+                    if (i < a.M && v < a.R) dst[v2 * 4 + q] = *reinterpret_cast<const float4 *>(a.z + (size_t)i * a.R + v);
                 }
         };
-        zfetch(0, zc[0]);
-        zfetch(1, zc[1]);
-        zfetch(2, zc[2]);
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int i = (ib0 + wi * 4 + it) * 32 + lne;
-            float4(&xs)[16] = zc[it % 3];
+        for (int ib = 0; ib < ZD - 1; ++ib) zfetch(ib, zc[ib]);
+#pragma unroll
+        for (int ib = 0; ib < 8; ++ib) {
+            if (ib + ZD - 1 < 8) zfetch(ib + ZD - 1, zc[(ib + ZD - 1) % ZD]);
+            const int i = (ib0 + ib) * 32 + lne;
+            float4(&xs)[8] = zc[ib % ZD];
             Part pt = part_identity();
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4)
+            for (int v2 = 0; v2 < 2; ++v2)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const int v = (rb0 + wv * 4 + v4) * 32 + 8 * q + 4 * lh;
-                    float4 &x4 = xs[v4 * 4 + q];
-                    x4.x += acc[v4][it][4 * q + 0];
-                    x4.y += acc[v4][it][4 * q + 1];
-                    x4.z += acc[v4][it][4 * q + 2];
-                    x4.w += acc[v4][it][4 * q + 3];
+                    const int v = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh;
+                    float4 &x4 = xs[v2 * 4 + q];
+                    x4.x += acc[v2][ib][4 * q + 0];
+                    x4.y += acc[v2][ib][4 * q + 1];
+                    x4.z += acc[v2][ib][4 * q + 2];
+                    x4.w += acc[v2][ib][4 * q + 3];
                     if (i < a.M && v < a.R) *reinterpret_cast<float4 *>(a.z + (size_t)i * a.R + v) = x4;
                     if (v < a.R) {
                         if (x4.x > pt.m) { pt.m = x4.x; pt.i = v; }
@@ -297,14 +295,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 }
             float sum = 0.f;
 #pragma unroll
-            for (int v4 = 0; v4 < 4; ++v4)
+            for (int v2 = 0; v2 < 2; ++v2)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    const bool ok = (rb0 + wv * 4 + v4) * 32 + 8 * q + 4 * lh < a.R;
-                    const float4 x4 = xs[v4 * 4 + q];
+                    const bool ok = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh < a.R;
+                    const float4 x4 = xs[v2 * 4 + q];
                     if (ok) sum += (__expf(x4.x - pt.m) + __expf(x4.y - pt.m)) + (__expf(x4.z - pt.m) + __expf(x4.w - pt.m));
                 }
-            if (it == 0) zfetch(3, zc[0]);   // (its registers are free again)
             pt.s = sum;
             Part other;
             other.m = __shfl_xor(pt.m, 32);
@@ -312,16 +309,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
             other.i = __shfl_xor(pt.i, 32);
             pt = part_merge(pt, other);
             if (lh == 0) {
-                const int row = (wi * 4 + it) * 32 + lne;
-                red_m[wv * 256 + row] = pt.m;
-                red_s[wv * 256 + row] = pt.s;
-                red_i[wv * 256 + row] = pt.i;
+                const int row = ib * 32 + lne;
+                red_m[wave * 256 + row] = pt.m;
+                red_s[wave * 256 + row] = pt.s;
+                red_i[wave * 256 + row] = pt.i;
             }
         }
         __syncthreads();
         {
-            const Part pt = part_merge(Part{red_m[tid], red_s[tid], red_i[tid]},
-                                       Part{red_m[256 + tid], red_s[256 + tid], red_i[256 + tid]});
+            Part pt = {red_m[tid], red_s[tid], red_i[tid]};
+#pragma unroll
+            for (int w = 1; w < 4; ++w) pt = part_merge(pt, Part{red_m[w * 256 + tid], red_s[w * 256 + tid], red_i[w * 256 + tid]});
             const int i = ib0 * 32 + tid;
             if (i < a.M) {
                 a.pm[(size_t)vt * a.M + i] = pt.m;
