@@ -261,16 +261,14 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
 
 size_t lm_persist_lds_bytes() { return (size_t)2 * LM_STAGE * 16 + (size_t)2 * LM_WAVES * LM_ROWS * 12; }
 
+// Once per device (mrp_create): the kernel needs more than the default 64 KiB of dynamic LDS.
+hipError_t lm_persist_configure() {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(lm_persist_kernel),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lm_persist_lds_bytes());
+}
+
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st) {
-    static bool attr_set = false;
-    const size_t lds = lm_persist_lds_bytes();
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(lm_persist_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    hipLaunchKernelGGL(lm_persist_kernel, dim3(a.nWG), dim3(LM_THREADS), lds, st, a);
+    hipLaunchKernelGGL(lm_persist_kernel, dim3(a.nWG), dim3(LM_THREADS), lm_persist_lds_bytes(), st, a);
     return hipGetLastError();
 }
 

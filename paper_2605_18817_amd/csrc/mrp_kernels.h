@@ -124,11 +124,13 @@ __device__ __forceinline__ size_t act_chunk_index(int row, int c8, int nIb) {
 // ---- host-side launchers (defined in the .hip files) ----
 hipError_t launch_stream_gemm(const StreamGemmArgs &a, int epi, hipStream_t st);
 size_t stream_gemm_lds_bytes(int it);
+hipError_t stream_gemm_configure();   // once per device
 int stream_gemm_it(int M);   // activation row blocks per workgroup for M rows
 
 hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st);
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st);
 size_t lm_persist_lds_bytes();
+hipError_t lm_persist_configure();    // once per device
 
 hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, hipStream_t st);
 hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb,

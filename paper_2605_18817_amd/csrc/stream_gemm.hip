@@ -280,25 +280,37 @@ constexpr size_t lds_bytes() {
 }
 
 template <int IT, int EPI, bool VEC4>
+auto kernel_of() -> void (*)(const StreamGemmArgs) {
+    if constexpr (IT == 4) return stream_gemm_kernel4<EPI, VEC4>;
+    else return stream_gemm_kernel8<EPI, VEC4>;
+}
+
+template <int IT, int EPI, bool VEC4>
+hipError_t configure_inst() {
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(kernel_of<IT, EPI, VEC4>()),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes<IT>());
+}
+
+template <int IT, int EPI, bool VEC4>
 hipError_t launch_inst(const StreamGemmArgs &a, hipStream_t st) {
-    static bool attr_set = false;
-    void (*kern)(const StreamGemmArgs) = nullptr;
-    if constexpr (IT == 4) kern = stream_gemm_kernel4<EPI, VEC4>;
-    else kern = stream_gemm_kernel8<EPI, VEC4>;
-    const size_t lds = lds_bytes<IT>();
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
     const int nWG = a.nVt * a.nMg * a.nKs;
     const int per = (nWG + 7) / 8;
-    hipLaunchKernelGGL(kern, dim3(per * 8), dim3(256), lds, st, a);
+    hipLaunchKernelGGL((kernel_of<IT, EPI, VEC4>()), dim3(per * 8), dim3(256), lds_bytes<IT>(), st, a);
     return hipGetLastError();
 }
 
 }  // namespace
+
+// Once per device (mrp_create): the kernels need more than the default 64 KiB of dynamic LDS.
+hipError_t stream_gemm_configure() {
+    hipError_t e = configure_inst<4, EPI_PARTIAL, true>();
+    if (e == hipSuccess) e = configure_inst<8, EPI_PARTIAL, true>();
+    if (e == hipSuccess) e = configure_inst<4, EPI_LM, true>();
+    if (e == hipSuccess) e = configure_inst<4, EPI_LM, false>();
+    if (e == hipSuccess) e = configure_inst<8, EPI_LM, true>();
+    if (e == hipSuccess) e = configure_inst<8, EPI_LM, false>();
+    return e;
+}
 
 int stream_gemm_it(int M) { return M > 128 ? 8 : 4; }
 
