@@ -30,6 +30,7 @@ namespace mrp {
 namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
 __device__ __forceinline__ bf16x8 as_frag(const u32x4 &u) { return __builtin_bit_cast(bf16x8, u); }
 
 constexpr int TG_KB = 4;                    // 16-wide k blocks per step (64 k)
@@ -51,7 +52,8 @@ typedef __attribute__((address_space(3))) void *las_ptr;
 // flight for later steps are not drained.
 __device__ __forceinline__ void tg_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
-template <int EPI>
+// REM = 2 + (k steps - 2) % 3: the k steps left for the straight-line tail after the unrolled loop
+template <int EPI, int REM>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void tiled_gemm_kernel(
     const TiledGemmArgs a) {
     const int tid = threadIdx.x, lane = tid & 63;
@@ -150,19 +152,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     // among the MFMAs of the current one (one wave per SIMD: nothing else hides them)
     bf16x8 bf[2][8];
 
+    // Logit tile of the epilogue (EPI_LM): 8 slices of 32 activation rows x this wave's 64 vocabulary
+    // entries, 8 16-byte pieces per lane each.  A piece is always fetched (addresses clamped into
+    // the matrix; what lies outside is never used), so the number of requests per step is fixed.
+    // The first two slices are requested during the last two k steps, in place of the operand
+    // requests those steps no longer need (more would not fit the registers next to the k loop's).
+    constexpr int ZD = 6;                       // slice buffers: five slices in flight ahead of the one added
+    f32x4 zc[ZD][8];
+    const int zv_lane = (rb0 + wave * 2) * 32 + 4 * lh;     // + 32 v2 + 8 q
+    auto zpiece = [&](int ib, int pc) __attribute__((always_inline)) -> f32x4 {
+        int i = (ib0 + ib) * 32 + ln;
+        int v = zv_lane + 32 * (pc >> 2) + 8 * (pc & 3);
+        i = i < a.M ? i : a.M - 1;
+        v = v < a.R - 4 ? v : a.R - 4;          // (R % 4 == 0 on this path)
+        return *reinterpret_cast<const f32x4 *>(a.z + (size_t)i * a.R + v);
+    };
+
     // One k step.  A wave issues in order, and a memory request that finds the request queue full
     // holds up the MFMAs behind it, so the step's 16 requests are spread between its 64 MFMAs
     // (one ahead of every group of four but the first) instead of being issued in a burst.
     int kbw_n;
     const u32x4 *bp_n;
-    auto step = [&](auto par_c, auto guard_c, int st, const u32x4 *cur, u32x4 *after) __attribute__((always_inline)) {
+    auto step = [&](auto par_c, auto role_c, const u32x4 *cur, u32x4 *after) __attribute__((always_inline)) {
         constexpr int PAR = decltype(par_c)::value;   // st % 3: activation stage and weight register set
         constexpr int NS = (PAR + 2) % TG_DEPTH;      // set and stage (`after`) of step st + 2
-        constexpr bool GUARD = decltype(guard_c)::value;
+        // 0: the operands of the step after next are still to request, 1: second to last step,
+        // 2: last step
+        constexpr int role = decltype(role_c)::value;
         // (`after` was last read one step ago and every wave has passed the barrier since;
         //  past the end the last step is re-fetched, never used)
-        const bool live = !GUARD || st < nsteps;
-        if (live) {
+        constexpr bool live = true;
+        {
 #pragma unroll
             for (int ib = 0; ib < 8; ++ib) bf[0][ib] = as_frag(cur[ib * 64 + lane]);
         }
@@ -173,16 +193,23 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 const int c = kb * 4 + g4;             // group 0..15
                 if (c >= 1) {                          // requests 0..14 (15 goes with group 15, too)
                     const int rq = c - 1;
-                    if (rq & 1) {
-                        const int wl = rq >> 1;        // weight fragment 0..6 (7 below)
-                        areg[NS][wl >> 2][wl & 3] = asrc[wl >> 2][(size_t)(kbw_n + (wl & 3)) * 64];
-                    } else {
-                        const int ch = wave + 4 * (rq >> 1);   // chunk: k block ch / 8, row block ch % 8
-                        __builtin_amdgcn_global_load_lds(
-                            (gas_ptr)(bp_n + ((size_t)(ch >> 3) * a.nIb + (ch & 7)) * 64 + lane),
-                            (las_ptr)(after + ch * 64), 16, 0, 0);
+                    if constexpr (role == 0) {
+                        if (rq & 1) {
+                            const int wl = rq >> 1;        // weight fragment 0..6 (7 below)
+                            areg[NS][wl >> 2][wl & 3] = asrc[wl >> 2][(size_t)(kbw_n + (wl & 3)) * 64];
+                        } else {
+                            const int ch = wave + 4 * (rq >> 1);   // chunk: k block ch / 8, row block ch % 8
+                            __builtin_amdgcn_global_load_lds(
+                                (gas_ptr)(bp_n + ((size_t)(ch >> 3) * a.nIb + (ch & 7)) * 64 + lane),
+                                (las_ptr)(after + ch * 64), 16, 0, 0);
+                        }
+                        if (c == 15) areg[NS][1][3] = asrc[1][(size_t)(kbw_n + 3) * 64];
+                    } else if constexpr (EPI == EPI_LM) {
+                        if (rq < 8) {                      // second to last step: slice 0; last step: slice 1
+                            if constexpr (role == 1) zc[0][rq] = zpiece(0, rq);
+                            else zc[1][rq] = zpiece(1, rq);
+                        }
                     }
-                    if (c == 15) areg[NS][1][3] = asrc[1][(size_t)(kbw_n + 3) * 64];
                 }
                 if (live) {
                     if (kb + 1 < TG_KB) {
@@ -196,33 +223,43 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                         acc[v2][i0 + it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                             as_frag(areg[PAR][v2][kb]), bf[kb & 1][i0 + it], acc[v2][i0 + it], 0, 0, 0);
                 }
-                if (c == 0) {   // behind the first MFMAs: where step st + 2's operands are
+                if (c == 0 && role == 0) {   // behind the first MFMAs: where the operands of the step after next are
                     cursor_get(kbw_n, bp_n);
                     cursor_next();
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
-        TG_WAIT_PREV();
+        // the next step's operands (requested one step ago) are there once at most this step's 16
+        // requests are pending; the second to last step requests 8 logit pieces (none in the partial-sum kernel)
+        if constexpr (role == 1) __builtin_amdgcn_s_waitcnt(EPI == EPI_LM ? 0x0F78 : 0x0F70);   // vmcnt(8) / vmcnt(0)
+        else if constexpr (role == 0) TG_WAIT_PREV();
         tg_barrier();
     };
     {
-        using T = std::true_type;
-        using F = std::false_type;
-        int st = 0;
-        for (; st + TG_DEPTH <= nsteps; st += TG_DEPTH) {
-            step(std::integral_constant<int, 0>{}, F{}, st, tg_stage0, tg_stage2);
-            step(std::integral_constant<int, 1>{}, F{}, st + 1, tg_stage1, tg_stage0);
-            step(std::integral_constant<int, 2>{}, F{}, st + 2, tg_stage2, tg_stage1);
+        using P0 = std::integral_constant<int, 0>;
+        using P1 = std::integral_constant<int, 1>;
+        using P2 = std::integral_constant<int, 2>;
+        for (int st = 0; st + TG_DEPTH <= nsteps - 2; st += TG_DEPTH) {
+            step(P0{}, P0{}, tg_stage0, tg_stage2);
+            step(P1{}, P0{}, tg_stage1, tg_stage0);
+            step(P2{}, P0{}, tg_stage2, tg_stage1);
         }
-        if (st < nsteps) {   // the last one or two steps
-            step(std::integral_constant<int, 0>{}, T{}, st, tg_stage0, tg_stage2);
-            step(std::integral_constant<int, 1>{}, T{}, st + 1, tg_stage1, tg_stage0);
-            step(std::integral_constant<int, 2>{}, T{}, st + 2, tg_stage2, tg_stage1);
+        // the last REM steps (second template argument: 0 ordinary, 1 second to last, 2 last)
+        if constexpr (REM == 2) {
+            step(P0{}, P1{}, tg_stage0, tg_stage2);
+            step(P1{}, P2{}, tg_stage1, tg_stage0);
+        } else if constexpr (REM == 3) {
+            step(P0{}, P0{}, tg_stage0, tg_stage2);
+            step(P1{}, P1{}, tg_stage1, tg_stage0);
+            step(P2{}, P2{}, tg_stage2, tg_stage1);
+        } else {
+            step(P0{}, P0{}, tg_stage0, tg_stage2);
+            step(P1{}, P0{}, tg_stage1, tg_stage0);
+            step(P2{}, P1{}, tg_stage2, tg_stage1);
+            step(P0{}, P2{}, tg_stage0, tg_stage2);
         }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): the padded tail's LDS-direct loads have landed
-    tg_barrier();
 #undef TG_LOAD
 #undef TG_WAIT_PREV
 
@@ -252,45 +289,37 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         float *red_m = reinterpret_cast<float *>(tg_stage0);       // [4 waves][256 rows] (the stages are dead)
         float *red_s = red_m + 1024;
         int *red_i = reinterpret_cast<int *>(red_s + 1024);
-        // Five slices of the logit tile are in flight ahead of the one being added; the sum is
-        // formed in place in the fetched registers.
-        constexpr int ZD = 6;
-        float4 zc[ZD][8];
-        auto zfetch = [&](int ib, float4 (&dst)[8]) __attribute__((always_inline)) {
-            const int i = (ib0 + ib) * 32 + lne;
+        // Slices 0 and 1 were requested during the last two k steps; five slices are kept in flight
+        // ahead of the one being added; the sum is formed in place in the fetched registers.
+        auto zfetch = [&](int ib, f32x4 (&dst)[8]) __attribute__((always_inline)) {
 #pragma unroll
-            for (int v2 = 0; v2 < 2; ++v2)
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int v = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh;
-                    dst[v2 * 4 + q] = make_float4(0.f, 0.f, 0.f, 0.f);
-                    if (i < a.M && v < a.R) dst[v2 * 4 + q] = *reinterpret_cast<const float4 *>(a.z + (size_t)i * a.R + v);
-                }
+            for (int pc = 0; pc < 8; ++pc) dst[pc] = zpiece(ib, pc);
         };
-#pragma unroll
-        for (int ib = 0; ib < ZD - 1; ++ib) zfetch(ib, zc[ib]);
+        zfetch(2, zc[2]);
+        zfetch(3, zc[3]);
+        zfetch(4, zc[4]);
 #pragma unroll
         for (int ib = 0; ib < 8; ++ib) {
             if (ib + ZD - 1 < 8) zfetch(ib + ZD - 1, zc[(ib + ZD - 1) % ZD]);
             const int i = (ib0 + ib) * 32 + lne;
-            float4(&xs)[8] = zc[ib % ZD];
+            f32x4(&xs)[8] = zc[ib % ZD];
             Part pt = part_identity();
 #pragma unroll
             for (int v2 = 0; v2 < 2; ++v2)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int v = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh;
-                    float4 &x4 = xs[v2 * 4 + q];
-                    x4.x += acc[v2][ib][4 * q + 0];
-                    x4.y += acc[v2][ib][4 * q + 1];
-                    x4.z += acc[v2][ib][4 * q + 2];
-                    x4.w += acc[v2][ib][4 * q + 3];
-                    if (i < a.M && v < a.R) *reinterpret_cast<float4 *>(a.z + (size_t)i * a.R + v) = x4;
+                    f32x4 &x4 = xs[v2 * 4 + q];
+                    x4[0] += acc[v2][ib][4 * q + 0];
+                    x4[1] += acc[v2][ib][4 * q + 1];
+                    x4[2] += acc[v2][ib][4 * q + 2];
+                    x4[3] += acc[v2][ib][4 * q + 3];
+                    if (i < a.M && v < a.R) *reinterpret_cast<f32x4 *>(a.z + (size_t)i * a.R + v) = x4;
                     if (v < a.R) {
-                        if (x4.x > pt.m) { pt.m = x4.x; pt.i = v; }
-                        if (x4.y > pt.m) { pt.m = x4.y; pt.i = v + 1; }
-                        if (x4.z > pt.m) { pt.m = x4.z; pt.i = v + 2; }
-                        if (x4.w > pt.m) { pt.m = x4.w; pt.i = v + 3; }
+                        if (x4[0] > pt.m) { pt.m = x4[0]; pt.i = v; }
+                        if (x4[1] > pt.m) { pt.m = x4[1]; pt.i = v + 1; }
+                        if (x4[2] > pt.m) { pt.m = x4[2]; pt.i = v + 2; }
+                        if (x4[3] > pt.m) { pt.m = x4[3]; pt.i = v + 3; }
                     }
                 }
             float sum = 0.f;
@@ -299,8 +328,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const bool ok = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh < a.R;
-                    const float4 x4 = xs[v2 * 4 + q];
-                    if (ok) sum += (__expf(x4.x - pt.m) + __expf(x4.y - pt.m)) + (__expf(x4.z - pt.m) + __expf(x4.w - pt.m));
+                    const f32x4 x4 = xs[v2 * 4 + q];
+                    if (ok) sum += (__expf(x4[0] - pt.m) + __expf(x4[1] - pt.m)) + (__expf(x4[2] - pt.m) + __expf(x4[3] - pt.m));
                 }
             pt.s = sum;
             Part other;
@@ -330,20 +359,30 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     }
 }
 
-template <int EPI>
+template <int EPI, int REM>
 hipError_t launch_inst(const TiledGemmArgs &a, hipStream_t st) {
     const int nMgrp = (a.nMt + 3) / 4, nVch = (a.nVt + 7) / 8;
     const int nsb = nMgrp * nVch;
     const int per_xcd = (nsb + 7) / 8;          // super-blocks per XCD
     const int grid = per_xcd * 32 * 8;
-    hipLaunchKernelGGL(tiled_gemm_kernel<EPI>, dim3(grid), dim3(256), 0, st, a);
+    hipLaunchKernelGGL((tiled_gemm_kernel<EPI, REM>), dim3(grid), dim3(256), 0, st, a);
     return hipGetLastError();
+}
+
+template <int EPI>
+hipError_t launch_epi(const TiledGemmArgs &a, hipStream_t st) {
+    int nsteps = 0;
+    for (int sg = 0; sg < a.nseg; ++sg) nsteps += a.seg[sg].nkq * a.seg[sg].nplanes;
+    const int rem = 2 + (nsteps - 2) % 3;       // (at least two k steps: d >= 128)
+    if (rem == 2) return launch_inst<EPI, 2>(a, st);
+    if (rem == 3) return launch_inst<EPI, 3>(a, st);
+    return launch_inst<EPI, 4>(a, st);
 }
 
 }  // namespace
 
 hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st) {
-    return epi == EPI_LM ? launch_inst<EPI_LM>(a, st) : launch_inst<EPI_PARTIAL>(a, st);
+    return epi == EPI_LM ? launch_epi<EPI_LM>(a, st) : launch_epi<EPI_PARTIAL>(a, st);
 }
 
 }  // namespace mrp
