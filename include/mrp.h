@@ -89,7 +89,13 @@ typedef struct {
  *   run_state0   1: first reduce z and apply the reveal rule as state
  *                state_offset (the backbone's own reveal, Algorithm 2 line
  *                before the inner loop); 0: skip it and take cond_tok /
- *                protect_pos / masks as given */
+ *                protect_pos / masks as given
+ *   remask_mode  which confidence the remask rule compares with tau_remask:
+ *                0 the row's top-1 probability under the updated logits (the
+ *                definition of confidence, Section 2); 1 the probability the
+ *                updated logits give to the token that was revealed at that row
+ *                ("the confidence ... stays above tau", Section 3.4, read as a
+ *                statement about the revealed token); needs x_tok */
 typedef struct {
     float tau;
     int r_min;
@@ -100,6 +106,7 @@ typedef struct {
     int fresh_block;
     int state_offset;
     int run_state0;
+    int remask_mode;
 } mrp_reveal_cfg;
 
 /* Per-step state and outputs (device).  Slot k of tok/conf/lse is the local
@@ -116,7 +123,10 @@ typedef struct {
  *   draft_pos/tok    [B][K+1]    most confident new reveal of each local state
  *                                (position in block, token), -1 if none
  *   remasked         [(K+1)][M]  1 where a row was remasked at that state; may
- *                                be NULL */
+ *                                be NULL
+ *   x_tok            [M] in/out  token recorded when a row is revealed (what
+ *                                mrp_commit writes into the block); may be NULL
+ *                                unless remask_mode = 1 */
 typedef struct {
     int32_t *tok;
     float *conf;
@@ -127,6 +137,7 @@ typedef struct {
     int32_t *protect_pos;
     int32_t *draft_pos, *draft_tok;
     uint8_t *remasked;
+    int32_t *x_tok;
 } mrp_step_io;
 
 /* Create / destroy a context on the current device.  mrp_create allocates the
@@ -169,6 +180,16 @@ int mrp_chain_step(mrp_ctx *ctx, void *stream, int B, int K, const void *h, floa
 int mrp_remask(mrp_ctx *ctx, void *stream, int B, int state, const float *conf_new,
                float tau_remask, const int32_t *protect_pos, int8_t *revealed_at,
                uint8_t *masked, uint8_t *remasked_out);
+
+/* End of a denoising step (Algorithm 2: "x_t <- reveal ..."; Algorithm 4 returns
+ * the reveals that survived remasking): every row revealed in this step
+ * (revealed_at >= 0) is committed -- its recorded token x_tok goes into the
+ * block x_out, revealed_at becomes -2, and the row stays unmasked in later
+ * steps.  n_masked[b] = rows of sequence b still masked (the decode loop of a
+ * block ends when it is 0).  All pointers device; x_tok [M] in, revealed_at [M]
+ * in/out, masked [M] in, x_out [M] in/out, n_masked [B] out. */
+int mrp_commit(mrp_ctx *ctx, void *stream, int B, const int32_t *x_tok, int8_t *revealed_at,
+               const uint8_t *masked, int32_t *x_out, int32_t *n_masked);
 
 /* Speculative verification (Algorithm 3, "reject drafted positions where the
  * argmaxes differ"): for each sequence b and draft j < K,

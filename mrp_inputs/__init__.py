@@ -189,8 +189,10 @@ def hidden(cfg: Config, step: int = 0, seqs: Optional[Iterable[int]] = None) -> 
     return out
 
 
-def logits0(cfg: Config, seqs: Optional[Iterable[int]] = None, out: Optional[np.ndarray] = None) -> np.ndarray:
-    """Prior logit state ``z0``: fp32 [len(seqs)*L, V], N(0, 2) plus spikes."""
+def logits0(cfg: Config, seqs: Optional[Iterable[int]] = None, out: Optional[np.ndarray] = None,
+            step: int = 0) -> np.ndarray:
+    """Prior logit state ``z0``: fp32 [len(seqs)*L, V], N(0, 2) plus spikes.  ``step`` > 0 gives the
+    (independent) prior logits a stand-in backbone produces at a later denoising step."""
     s = _seqs(cfg, seqs)
     if out is None:
         out = np.empty((len(s) * cfg.L, cfg.V), dtype=np.float32)
@@ -198,11 +200,11 @@ def logits0(cfg: Config, seqs: Optional[Iterable[int]] = None, out: Optional[np.
     def one(j):
         b = s[j]
         blk = out[j * cfg.L:(j + 1) * cfg.L]
-        g = _rng(cfg.cid, T_Z, b)
+        g = _rng(cfg.cid, T_Z, b, step)
         g.standard_normal(out=blk, dtype=np.float32)
         blk *= np.float32(2.0)
         if cfg.spike_frac > 0.0:
-            gs = _rng(cfg.cid, T_SPIKE, b)
+            gs = _rng(cfg.cid, T_SPIKE, b, step)
             hit = gs.random(cfg.L) < cfg.spike_frac
             idx = gs.integers(0, cfg.V, cfg.L)
             hgt = gs.uniform(cfg.spike_lo, cfg.spike_hi, cfg.L).astype(np.float32)

@@ -31,7 +31,7 @@ class _Cfg(C.Structure):
                 ("rms_eps", C.c_double), ("tau", C.c_double), ("r_min", C.c_int),
                 ("max_accept", C.c_int), ("carry_hidden", C.c_int), ("tau_remask", C.c_double),
                 ("head_reveal", C.c_int), ("fresh_block", C.c_int), ("state_offset", C.c_int),
-                ("run_state0", C.c_int)]
+                ("run_state0", C.c_int), ("remask_mode", C.c_int)]
 
 
 _lib = None
@@ -60,9 +60,10 @@ def _chk(a, dtype, shape=None):
 
 
 def make_cfg(d, V, B, L, K, tau=0.9, r_min=1, max_accept=0, carry_hidden=1, tau_remask=-1.0,
-             head_reveal=1, fresh_block=1, state_offset=0, run_state0=1, rms_eps=1e-6) -> _Cfg:
+             head_reveal=1, fresh_block=1, state_offset=0, run_state0=1, rms_eps=1e-6,
+             remask_mode=0) -> _Cfg:
     return _Cfg(d, V, B, L, K, rms_eps, tau, r_min, max_accept, carry_hidden, tau_remask,
-                head_reveal, fresh_block, state_offset, run_state0)
+                head_reveal, fresh_block, state_offset, run_state0, remask_mode)
 
 
 def bf16_round(x: np.ndarray) -> np.ndarray:
@@ -154,10 +155,11 @@ class ChainOut:
     remasked: np.ndarray     # [(K+1)][M]
     y: Optional[np.ndarray]  # [K][M][d] bf16-rounded LM-head operand
     gap: np.ndarray          # [(K+1)][M] top-2 logit gap of every state
+    x_tok: Optional[np.ndarray] = None   # [M] token recorded when a position was revealed (-1: none)
 
 
 def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, revealed_at=None,
-               cond_tok=None, protect_pos=None, dump_y=False) -> ChainOut:
+               cond_tok=None, protect_pos=None, dump_y=False, x_tok=None) -> ChainOut:
     """One chain step.  ``z`` [M][V] and ``hrun`` [M][d] float64 are copied, not modified."""
     M, d, V, K, B = cfg.B * cfg.L, cfg.d, cfg.V, cfg.K, cfg.B
     assert len(heads) == K
@@ -180,7 +182,57 @@ def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, reveal
     rem = np.zeros((K + 1, M), np.uint8)
     y = np.empty((K, M, d)) if dump_y else None
     gap = np.full((K + 1, M), np.inf)
+    x_tok = np.full(M, -1, np.int32) if x_tok is None else np.array(x_tok, np.int32)
     lib().orc_chain_step(C.byref(cfg), _p(E), _p(W_lm), w1s, w2s, gs, _p(z), _p(hrun), _p(tok), _p(conf),
                          _p(lse), _p(masked), _p(revealed_at), _p(cond_tok), _p(protect_pos), _p(dpos),
-                         _p(dtok), _p(rem), _p(y), _p(gap))
-    return ChainOut(z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos, dpos, dtok, rem, y, gap)
+                         _p(dtok), _p(rem), _p(y), _p(gap), _p(x_tok))
+    return ChainOut(z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos, dpos, dtok, rem, y, gap,
+                    x_tok)
+
+
+def token_prob(z, lse, x_tok) -> np.ndarray:
+    """softmax(z[i])[x_tok[i]] per row (0 where x_tok[i] < 0)."""
+    z = _chk(np.ascontiguousarray(z, dtype=np.float64), np.float64)
+    M, V = z.shape
+    lse = _chk(np.ascontiguousarray(lse, dtype=np.float64), np.float64, (M,))
+    x_tok = _chk(np.ascontiguousarray(x_tok, dtype=np.int32), np.int32, (M,))
+    p = np.empty(M)
+    lib().orc_token_prob(_p(z), M, V, _p(lse), _p(x_tok), _p(p))
+    return p
+
+
+def commit(B, L, x_tok, revealed_at, masked, x_out):
+    """End of a denoising step.  Returns (x_out, revealed_at, n_masked); inputs are copied."""
+    M = B * L
+    x_tok = _chk(np.ascontiguousarray(x_tok, dtype=np.int32), np.int32, (M,))
+    revealed_at = np.array(revealed_at, np.int8); masked = np.array(masked, np.uint8)
+    x_out = np.array(x_out, np.int32)
+    n = np.empty(B, np.int32)
+    lib().orc_commit(B, L, _p(x_tok), _p(revealed_at), _p(masked), _p(x_out), _p(n))
+    return x_out, revealed_at, n
+
+
+def decode_block(cfg: _Cfg, E, W_lm, heads: Sequence, backbone, max_steps=None):
+    """Decode one block per sequence to completion (Algorithm 2 with tau >= 1 / r_min = r, Algorithm 4
+    with tau_remask set): every denoising step asks ``backbone(step, x_out, masked)`` for the
+    prior logits z [M][V] and hidden states h [M][d] of that step, runs one chain step on the
+    still-masked positions, and commits what it revealed.  Returns (x_out, steps, history) where
+    history[t] is the ChainOut of step t."""
+    B, L = cfg.B, cfg.L
+    M = B * L
+    x_out = np.full(M, -1, np.int32)
+    masked = np.ones(M, np.uint8)
+    revealed_at = np.full(M, -1, np.int8)
+    history = []
+    max_steps = L if max_steps is None else max_steps
+    steps = 0
+    step_cfg = _Cfg.from_buffer_copy(cfg)
+    step_cfg.fresh_block = 0
+    while masked.any() and steps < max_steps:
+        z, h = backbone(steps, x_out.copy(), masked.copy())
+        out = chain_step(step_cfg, E, W_lm, heads, z, h, masked=masked, revealed_at=revealed_at)
+        x_out, revealed_at, _ = commit(B, L, out.x_tok, out.revealed_at, out.masked, x_out)
+        masked = out.masked
+        history.append(out)
+        steps += 1
+    return x_out, steps, history

@@ -21,6 +21,13 @@
  *   - max-accept cap m = min(max(floor(0.7 n), 5), L) (Section 4.4).
  *   - remask: positions revealed earlier in this step whose updated
  *       confidence is below the remask threshold (Section 3.4, Algorithm 4).
+ *       Variant (remask_mode 1): the confidence compared is the probability
+ *       the updated logits assign to the token that was revealed at that
+ *       position ("stays above tau" read as a statement about that token),
+ *       not the row's top-1 probability.
+ *   - commit: at the end of a denoising step the revealed tokens are written
+ *       into the block and those positions stay unmasked in later steps
+ *       (Algorithm 2: x_t <- reveal; Algorithm 4 returns R after remasking).
  *   - verify: a draft is accepted where the verifier's argmax equals the
  *       drafted token (Algorithm 3); the accepted length is the longest
  *       all-matching prefix of the draft list.
@@ -64,6 +71,8 @@ typedef struct {
     int fresh_block;     /* 1: state 0 starts from an all-masked block       */
     int state_offset;    /* heads run as states offset+1 .. offset+K          */
     int run_state0;      /* 1: reduce z and reveal (state 0) before the heads */
+    int remask_mode;     /* 0: remask on the row's top-1 probability; 1: on the probability the updated
+                            logits give to the token that was revealed there */
 } orc_cfg;
 
 /* threads the parallel loops will use */
@@ -255,6 +264,30 @@ void orc_remask(int B, int L, int state, const double *conf, double tau_remask,
         }
 }
 
+/* p[i] = softmax(z[i,:])[x_tok[i]] = exp(z[i][x_tok[i]] - lse[i]); 0 where no token is recorded. */
+void orc_token_prob(const double *z, int M, int V, const double *lse, const int32_t *x_tok, double *p) {
+    for (int i = 0; i < M; ++i) {
+        const int t = x_tok[i];
+        p[i] = (t >= 0 && t < V) ? exp(z[(size_t)i * V + t] - lse[i]) : 0.0;
+    }
+}
+
+/* End of a denoising step: every position revealed in this step (revealed_at >= 0) is committed:
+ * its token goes into the block (x_out), it is marked -2 (committed earlier) and stays unmasked.
+ * n_masked[b] = positions of sequence b still masked. */
+void orc_commit(int B, int L, const int32_t *x_tok, int8_t *revealed_at, const uint8_t *masked,
+                int32_t *x_out, int32_t *n_masked) {
+    for (int b = 0; b < B; ++b) {
+        int n = 0;
+        for (int p = 0; p < L; ++p) {
+            const size_t i = (size_t)b * L + p;
+            if (revealed_at[i] >= 0) { x_out[i] = x_tok[i]; revealed_at[i] = -2; }
+            if (masked[i]) ++n;
+        }
+        n_masked[b] = n;
+    }
+}
+
 /* Verify K drafts per sequence against verifier logits [B][L][V]. */
 void orc_verify_accept(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
                        const int32_t *draft_tok, uint8_t *match, int32_t *accept_len,
@@ -290,14 +323,17 @@ void orc_verify_accept(int B, int L, int V, int K, const float *verify, const in
  *   draft_pos/draft_tok [B][K+1] (column = local state index)
  *   remasked [(K+1)][M] (may be NULL)
  *   y_dump  [K][M][d] (may be NULL)
- *   gap     [(K+1)][M] top-2 logit gap per state (may be NULL) */
+ *   gap     [(K+1)][M] top-2 logit gap per state (may be NULL)
+ *   x_tok   [M] in/out: token recorded when a position is revealed (may be NULL unless
+ *           remask_mode is 1) */
 void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
                     const uint16_t *const *W1, const uint16_t *const *W2,
                     const uint16_t *const *gamma, double *z, double *hrun, int32_t *tok,
                     double *conf, double *lse, uint8_t *masked, int8_t *revealed_at,
                     int32_t *cond_tok, int32_t *protect_pos, int32_t *draft_pos,
-                    int32_t *draft_tok, uint8_t *remasked, double *y_dump, double *gap) {
+                    int32_t *draft_tok, uint8_t *remasked, double *y_dump, double *gap, int32_t *x_tok) {
     const int M = c->B * c->L, K = c->K, B = c->B;
+    double *ptok = (c->remask_mode == 1) ? (double *)malloc(sizeof(double) * M) : NULL;
     int32_t *dp = (int32_t *)malloc(sizeof(int32_t) * B);
     int32_t *dt = (int32_t *)malloc(sizeof(int32_t) * B);
     double *y = (double *)malloc(sizeof(double) * (size_t)M * c->d);
@@ -307,9 +343,11 @@ void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
 
     if (c->run_state0) {
         if (c->fresh_block)
-            for (int i = 0; i < M; ++i) { masked[i] = 1; revealed_at[i] = -1; }
+            for (int i = 0; i < M; ++i) { masked[i] = 1; revealed_at[i] = -1; if (x_tok) x_tok[i] = -1; }
         orc_reduce_rows(z, M, c->V, tok, conf, lse, gap);
         orc_reveal(c, c->state_offset, conf, tok, masked, revealed_at, dp, dt, cond_tok, protect_pos);
+        if (x_tok)
+            for (int i = 0; i < M; ++i) if (revealed_at[i] == c->state_offset) x_tok[i] = tok[i];
         for (int b = 0; b < B; ++b) { draft_pos[b * (K + 1)] = dp[b]; draft_tok[b * (K + 1)] = dt[b]; }
     }
     for (int k = 1; k <= K; ++k) {
@@ -323,13 +361,19 @@ void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
             orc_reveal(c, state, conf + (size_t)k * M, tok + (size_t)k * M, masked, revealed_at,
                        dp, dt, cond_tok, NULL);
             for (int b = 0; b < B; ++b) { draft_pos[b * (K + 1) + k] = dp[b]; draft_tok[b * (K + 1) + k] = dt[b]; }
+            if (x_tok)
+                for (int i = 0; i < M; ++i) if (revealed_at[i] == state) x_tok[i] = tok[(size_t)k * M + i];
         }
         if (c->tau_remask >= 0.0) {
             uint8_t *rm = remasked ? remasked + (size_t)k * M : (uint8_t *)malloc(M);
-            orc_remask(B, c->L, state, conf + (size_t)k * M, c->tau_remask, protect_pos, masked,
-                       revealed_at, rm);
+            const double *cr = conf + (size_t)k * M;
+            if (c->remask_mode == 1) {
+                orc_token_prob(z, M, c->V, lse + (size_t)k * M, x_tok, ptok);
+                cr = ptok;
+            }
+            orc_remask(B, c->L, state, cr, c->tau_remask, protect_pos, masked, revealed_at, rm);
             if (!remasked) free(rm);
         }
     }
-    free(dp); free(dt); free(y);
+    free(dp); free(dt); free(y); free(ptok);
 }

@@ -10,7 +10,7 @@ from . import build as _build
 
 EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
-    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_verify_accept",
+    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept",
     "mrp_profile_enable", "mrp_profile_read",
 ]
 
@@ -33,13 +33,14 @@ class _Head(C.Structure):
 class _RevealCfg(C.Structure):
     _fields_ = [("tau", C.c_float), ("r_min", C.c_int), ("max_accept", C.c_int), ("carry_hidden", C.c_int),
                 ("tau_remask", C.c_float), ("head_reveal", C.c_int), ("fresh_block", C.c_int),
-                ("state_offset", C.c_int), ("run_state0", C.c_int)]
+                ("state_offset", C.c_int), ("run_state0", C.c_int), ("remask_mode", C.c_int)]
 
 
 class _StepIO(C.Structure):
     _fields_ = [("tok", C.c_void_p), ("conf", C.c_void_p), ("lse", C.c_void_p), ("revealed_at", C.c_void_p),
                 ("masked", C.c_void_p), ("cond_tok", C.c_void_p), ("protect_pos", C.c_void_p),
-                ("draft_pos", C.c_void_p), ("draft_tok", C.c_void_p), ("remasked", C.c_void_p)]
+                ("draft_pos", C.c_void_p), ("draft_tok", C.c_void_p), ("remasked", C.c_void_p),
+                ("x_tok", C.c_void_p)]
 
 
 _lib = None
@@ -71,6 +72,8 @@ def load_library():
                                    C.POINTER(_StepIO)]
     lib.mrp_remask.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_float, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.mrp_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                               C.c_void_p]
     lib.mrp_verify_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.mrp_profile_enable.argtypes = [C.c_void_p, C.c_int]
@@ -129,6 +132,7 @@ class RevealCfg:
     fresh_block: int = 1
     state_offset: int = 0
     run_state0: int = 1
+    remask_mode: int = 0
 
 
 class StepIO:
@@ -148,11 +152,12 @@ class StepIO:
         self.draft_pos = torch.full((B, K + 1), -1, dtype=torch.int32, device=device)
         self.draft_tok = torch.full((B, K + 1), -1, dtype=torch.int32, device=device)
         self.remasked = torch.zeros((K + 1, M), dtype=torch.uint8, device=device)
+        self.x_tok = torch.full((M,), -1, dtype=torch.int32, device=device)
 
     def c_struct(self) -> _StepIO:
         return _StepIO(_ptr(self.tok), _ptr(self.conf), _ptr(self.lse), _ptr(self.revealed_at), _ptr(self.masked),
                        _ptr(self.cond_tok), _ptr(self.protect_pos), _ptr(self.draft_pos), _ptr(self.draft_tok),
-                       _ptr(self.remasked))
+                       _ptr(self.remasked), _ptr(self.x_tok))
 
 
 class MrpContext:
@@ -200,7 +205,7 @@ class MrpContext:
         if len(heads) < K <= MRP_MAX_HEADS:
             raise MrpError("fewer heads than K")
         ccfg = _RevealCfg(cfg.tau, cfg.r_min, cfg.max_accept, cfg.carry_hidden, cfg.tau_remask, cfg.head_reveal,
-                          cfg.fresh_block, cfg.state_offset, cfg.run_state0)
+                          cfg.fresh_block, cfg.state_offset, cfg.run_state0, cfg.remask_mode)
         cio = io.c_struct()
         rc = self.lib.mrp_chain_step(self._h, _stream(), B, K, _ptr(h), _ptr(h_run), _ptr(E), _ptr(W_lm_packed),
                                      harr, _ptr(z), C.byref(ccfg), C.byref(cio))
@@ -211,6 +216,37 @@ class MrpContext:
         rc = self.lib.mrp_remask(self._h, _stream(), B, state, _ptr(conf_new), tau_remask, _ptr(protect_pos),
                                  _ptr(revealed_at), _ptr(masked), _ptr(remasked_out))
         return self._check(rc, "mrp_remask") if check else rc
+
+    def commit(self, B: int, x_tok, revealed_at, masked, x_out, n_masked, check: bool = True) -> int:
+        rc = self.lib.mrp_commit(self._h, _stream(), B, _ptr(x_tok), _ptr(revealed_at), _ptr(masked), _ptr(x_out),
+                                 _ptr(n_masked))
+        return self._check(rc, "mrp_commit") if check else rc
+
+    def decode_block(self, B: int, K: int, backbone, E, W_lm_packed, heads: Sequence[Head], cfg: RevealCfg,
+                     max_steps: Optional[int] = None):
+        """Decode one block per sequence to completion: each denoising step takes the prior logits
+        ``z`` (fp32 [M][V], device) and hidden states ``h`` (bf16 [M][d], device) from
+        ``backbone(step, x_out, masked)``, runs one chain step on the still-masked rows and commits
+        what it revealed (mrp_commit).  Only the count of masked rows comes back to the host, once
+        per step, to end the loop.  Returns (x_out [M] int32 device, steps, io)."""
+        import torch
+        L = self.L
+        M = B * L
+        io = StepIO(B, L, K)
+        x_out = torch.full((M,), -1, dtype=torch.int32, device="cuda")
+        n_masked = torch.empty((B,), dtype=torch.int32, device="cuda")
+        h_run = torch.empty((M, self.d), dtype=torch.float32, device="cuda")
+        step_cfg = RevealCfg(**{**cfg.__dict__, "fresh_block": 0})
+        max_steps = L if max_steps is None else max_steps
+        steps = 0
+        while steps < max_steps:
+            z, h = backbone(steps, x_out, io.masked)
+            self.chain_step(B, K, h, h_run, E, W_lm_packed, heads, z, step_cfg, io)
+            self.commit(B, io.x_tok, io.revealed_at, io.masked, x_out, n_masked)
+            steps += 1
+            if int(n_masked.sum().item()) == 0:
+                break
+        return x_out, steps, io
 
     def verify_accept(self, B: int, K: int, verify, draft_pos, draft_tok, draft_stride: int, match, accept_len,
                       correction_tok, check: bool = True) -> int:

@@ -228,8 +228,11 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
         return fail(c, MRP_ERR_NULL, "mrp_chain_step: required mrp_step_io pointer is NULL");
     const int L = c->dims.block_len, d = c->dims.d, V = c->dims.V;
     if (B < 0 || K < 0 || K > MRP_MAX_HEADS) return fail(c, MRP_ERR_SHAPE, "B=%d K=%d out of range", B, K);
-    if (cfg->r_min < 0 || cfg->state_offset < 0 || cfg->state_offset + K > 120 || !(cfg->tau == cfg->tau))
+    if (cfg->r_min < 0 || cfg->state_offset < 0 || cfg->state_offset + K > 120 || !(cfg->tau == cfg->tau) ||
+        cfg->remask_mode < 0 || cfg->remask_mode > 1)
         return fail(c, MRP_ERR_SHAPE, "bad reveal configuration");
+    if (cfg->remask_mode == 1 && cfg->tau_remask >= 0.f && !io->x_tok)
+        return fail(c, MRP_ERR_NULL, "remask_mode 1 needs mrp_step_io.x_tok");
     const long Ml = (long)B * L;
     if (Ml > c->dims.max_rows) return fail(c, MRP_ERR_WORKSPACE, "rows %ld exceed max_rows %d", Ml, c->dims.max_rows);
     for (int k = 0; k < K; ++k) {
@@ -258,6 +261,7 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
     sa.cond_tok = io->cond_tok; sa.protect_pos = io->protect_pos;
     sa.draft_stride = K + 1;
     sa.xe = c->XE; sa.nIb = c->nIb;
+    sa.x_tok = io->x_tok; sa.remask_mode = cfg->remask_mode; sa.z = z;
 
     if (cfg->run_state0) {
         int nT0 = 0;
@@ -407,6 +411,18 @@ int mrp_remask(mrp_ctx *c, void *stream, int B, int state, const float *conf_new
     if (B == 0) return MRP_OK;
     HIP_TRY(c, launch_remask(B, c->dims.block_len, state, conf_new, tau_remask, protect_pos, revealed_at, masked,
                              remasked_out, static_cast<hipStream_t>(stream)));
+    return MRP_OK;
+}
+
+int mrp_commit(mrp_ctx *c, void *stream, int B, const int32_t *x_tok, int8_t *revealed_at, const uint8_t *masked,
+               int32_t *x_out, int32_t *n_masked) {
+    if (!c) return MRP_ERR_NULL;
+    if (!x_tok || !revealed_at || !masked || !x_out || !n_masked) return fail(c, MRP_ERR_NULL, "mrp_commit: NULL pointer");
+    if (B < 0 || (long)B * c->dims.block_len > c->dims.max_rows)
+        return fail(c, MRP_ERR_SHAPE, "mrp_commit: B=%d out of range", B);
+    if (B == 0) return MRP_OK;
+    HIP_TRY(c, launch_commit(B, c->dims.block_len, x_tok, revealed_at, masked, x_out, n_masked,
+                             static_cast<hipStream_t>(stream)));
     return MRP_OK;
 }
 

@@ -164,6 +164,9 @@ struct SelectArgs {
     int32_t *draft_pos, *draft_tok;  // this state's column, stride draft_stride
     int draft_stride;
     uint8_t *remasked;      // this state's slot [M] or nullptr
+    int32_t *x_tok;         // [M] token recorded at reveal, or nullptr
+    int remask_mode;        // 1: remask on the probability of the recorded token (needs z, x_tok)
+    const float *z;         // [M][V] updated logits (remask_mode 1)
     const uint16_t *E;      // embedding rows to gather for the next head (nullptr: skip)
     uint4 *xe;
     int nIb;
@@ -172,6 +175,8 @@ hipError_t launch_reduce_rows(const float *z, int M, int V, float *pm, float *ps
                               hipStream_t st);
 int reduce_rows_tiles(int V);
 hipError_t launch_merge_select(const SelectArgs &a, hipStream_t st);
+hipError_t launch_commit(int B, int L, const int32_t *x_tok, int8_t *revealed_at, const uint8_t *masked,
+                         int32_t *x_out, int32_t *n_masked, hipStream_t st);
 hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_remask,
                          const int32_t *protect_pos, int8_t *revealed_at, uint8_t *masked,
                          uint8_t *remasked, hipStream_t st);

@@ -100,8 +100,8 @@ __device__ __forceinline__ bool more_confident(const float *conf, int a, int b) 
 }
 
 __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
-    __shared__ float s_conf[MAX_L];
-    __shared__ int s_tok[MAX_L];
+    __shared__ float s_conf[MAX_L], s_lse[MAX_L];
+    __shared__ int s_tok[MAX_L], s_xtok[MAX_L];
     __shared__ uint8_t s_mk[MAX_L], s_rem[MAX_L];
     __shared__ int8_t s_ra[MAX_L];
     __shared__ int s_gather;
@@ -113,6 +113,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
     if (threadIdx.x < L) {
         s_mk[threadIdx.x] = a.fresh ? (uint8_t)1 : a.masked[b * L + threadIdx.x];
         s_ra[threadIdx.x] = a.fresh ? (int8_t)-1 : a.revealed_at[b * L + threadIdx.x];
+        s_xtok[threadIdx.x] = (a.x_tok && !a.fresh) ? a.x_tok[b * L + threadIdx.x] : -1;
     }
     if (threadIdx.x == 0) {
         in_cond = a.cond_tok[b];
@@ -143,7 +144,9 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
             const float conf = 1.0f / pt.s;
             a.tok[i] = pt.i;
             a.conf[i] = conf;
-            a.lse[i] = pt.m + logf(pt.s);
+            const float lse = pt.m + logf(pt.s);
+            a.lse[i] = lse;
+            s_lse[p] = lse;
             s_conf[p] = conf;
             s_tok[p] = pt.i;
         }
@@ -172,7 +175,9 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
                 if (ns > m) ns = m;
             }
             if (ns < a.r_min) ns = a.r_min < nc ? a.r_min : nc;
-            for (int x = 0; x < ns; ++x) { s_mk[cand[x]] = 0; s_ra[cand[x]] = (int8_t)a.state; }
+            for (int x = 0; x < ns; ++x) {
+                s_mk[cand[x]] = 0; s_ra[cand[x]] = (int8_t)a.state; s_xtok[cand[x]] = s_tok[cand[x]];
+            }
             if (ns > 0) {
                 dpos = cand[0];
                 dtok = s_tok[cand[0]];
@@ -187,7 +192,14 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
             uint8_t rem = 0;
             if (a.tau_remask >= 0.f) {
                 const int r = s_ra[p];
-                if (r >= 0 && r <= a.state - 1 && p != prot && s_conf[p] < a.tau_remask) {
+                float cr = s_conf[p];
+                if (a.remask_mode == 1 && r >= 0 && r <= a.state - 1) {
+                    // probability of the token that was revealed here under the updated logits
+                    int t = s_xtok[p];
+                    t = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
+                    cr = (s_xtok[p] >= 0) ? expf(a.z[(size_t)(b * L + p) * a.V + t] - s_lse[p]) : 0.f;
+                }
+                if (r >= 0 && r <= a.state - 1 && p != prot && cr < a.tau_remask) {
                     s_mk[p] = 1; s_ra[p] = -1; rem = 1;
                 }
             }
@@ -201,6 +213,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
         a.masked[b * L + threadIdx.x] = s_mk[threadIdx.x];
         a.revealed_at[b * L + threadIdx.x] = s_ra[threadIdx.x];
         if (a.remasked) a.remasked[b * L + threadIdx.x] = s_rem[threadIdx.x];
+        if (a.x_tok) a.x_tok[b * L + threadIdx.x] = s_xtok[threadIdx.x];
     }
     if (a.E != nullptr) {  // embedding row that conditions the next head
         const int C8 = a.d >> 3;
@@ -212,6 +225,26 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
             for (int p = 0; p < L; ++p) a.xe[act_chunk_index(b * L + p, c8, a.nIb)] = v;
         }
     }
+}
+
+// End of a denoising step: commit this step's reveals (one workgroup per sequence, one lane per row).
+__global__ __launch_bounds__(64) void commit_kernel(int L, const int32_t *__restrict__ x_tok,
+                                                    int8_t *__restrict__ revealed_at,
+                                                    const uint8_t *__restrict__ masked, int32_t *__restrict__ x_out,
+                                                    int32_t *__restrict__ n_masked) {
+    const int b = blockIdx.x, p = threadIdx.x;
+    int m = 0;
+    if (p < L) {
+        const int i = b * L + p;
+        if (revealed_at[i] >= 0) {
+            x_out[i] = x_tok[i];
+            revealed_at[i] = -2;
+        }
+        m = masked[i] ? 1 : 0;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) m += __shfl_xor(m, off);
+    if (p == 0) n_masked[b] = m;
 }
 
 __global__ __launch_bounds__(64) void remask_kernel(int B, int L, int state, const float *__restrict__ conf,
@@ -322,6 +355,12 @@ hipError_t launch_reduce_rows(const float *z, int M, int V, float *pm, float *ps
 
 hipError_t launch_merge_select(const SelectArgs &a, hipStream_t st) {
     hipLaunchKernelGGL(merge_select_kernel, dim3(a.B), dim3(256), 0, st, a);
+    return hipGetLastError();
+}
+
+hipError_t launch_commit(int B, int L, const int32_t *x_tok, int8_t *revealed_at, const uint8_t *masked,
+                         int32_t *x_out, int32_t *n_masked, hipStream_t st) {
+    hipLaunchKernelGGL(commit_kernel, dim3(B), dim3(64), 0, st, L, x_tok, revealed_at, masked, x_out, n_masked);
     return hipGetLastError();
 }
 

@@ -86,7 +86,7 @@ def io_to_host(io: mrp.StepIO) -> SimpleNamespace:
                            revealed_at=io.revealed_at.cpu().numpy(), masked=io.masked.cpu().numpy(),
                            cond_tok=io.cond_tok.cpu().numpy(), protect_pos=io.protect_pos.cpu().numpy(),
                            draft_pos=io.draft_pos.cpu().numpy(), draft_tok=io.draft_tok.cpu().numpy(),
-                           remasked=io.remasked.cpu().numpy())
+                           remasked=io.remasked.cpu().numpy(), x_tok=io.x_tok.cpu().numpy())
 
 
 @dataclass
@@ -97,7 +97,7 @@ class OracleRun:
 
 
 def oracle_chain(prob: Problem, z0_rows: np.ndarray, hrun_rows: np.ndarray, rcfg: mrp.RevealCfg, K: int,
-                 masked=None, revealed_at=None, cond_tok=None, protect_pos=None, heads=None) -> OracleRun:
+                 masked=None, revealed_at=None, cond_tok=None, protect_pos=None, heads=None, x_tok=None) -> OracleRun:
     """Oracle chain on the given rows (whole sequences), one head per call so that
     every intermediate state is kept.  hrun_rows: float64 [rows][d]."""
     cfg = prob.cfg
@@ -111,17 +111,20 @@ def oracle_chain(prob: Problem, z0_rows: np.ndarray, hrun_rows: np.ndarray, rcfg
     gap = np.full((K + 1, M), np.inf); rem = np.zeros((K + 1, M), np.uint8)
     dpos = np.full((Bs, K + 1), -1, np.int32); dtok = np.full((Bs, K + 1), -1, np.int32)
     snaps = []
-    st = dict(masked=masked, revealed_at=revealed_at, cond_tok=cond_tok, protect_pos=protect_pos)
+    st = dict(masked=masked, revealed_at=revealed_at, cond_tok=cond_tok, protect_pos=protect_pos, x_tok=x_tok)
+    ptok = np.ones((K + 1, M))   # probability of the recorded token under each state's logits (remask_mode 1)
+    rmode = getattr(rcfg, "remask_mode", 0)
 
     def mk(Kc, offset, run0, fresh):
         return orc.make_cfg(cfg.d, cfg.V, Bs, L, Kc, tau=rcfg.tau, r_min=rcfg.r_min, max_accept=rcfg.max_accept,
                             carry_hidden=rcfg.carry_hidden, tau_remask=rcfg.tau_remask,
-                            head_reveal=rcfg.head_reveal, fresh_block=fresh, state_offset=offset, run_state0=run0)
+                            head_reveal=rcfg.head_reveal, fresh_block=fresh, state_offset=offset, run_state0=run0,
+                            remask_mode=rmode)
 
     def snap(o):
         snaps.append(SimpleNamespace(z=o.z.copy(), hrun=o.hrun.copy(), masked=o.masked.copy(),
                                      revealed_at=o.revealed_at.copy(), cond_tok=o.cond_tok.copy(),
-                                     protect_pos=o.protect_pos.copy()))
+                                     protect_pos=o.protect_pos.copy(), x_tok=o.x_tok.copy()))
 
     off = rcfg.state_offset
     if rcfg.run_state0:
@@ -133,17 +136,20 @@ def oracle_chain(prob: Problem, z0_rows: np.ndarray, hrun_rows: np.ndarray, rcfg
                             masked=np.ones(M, np.uint8) if masked is None else np.array(masked, np.uint8),
                             revealed_at=np.full(M, -1, np.int8) if revealed_at is None else np.array(revealed_at, np.int8),
                             cond_tok=np.zeros(Bs, np.int32) if cond_tok is None else np.array(cond_tok, np.int32),
-                            protect_pos=np.full(Bs, -1, np.int32) if protect_pos is None else np.array(protect_pos, np.int32))
+                            protect_pos=np.full(Bs, -1, np.int32) if protect_pos is None else np.array(protect_pos, np.int32),
+                            x_tok=np.full(M, -1, np.int32) if x_tok is None else np.array(x_tok, np.int32))
     snap(o)
     for k in range(1, K + 1):
         o = orc.chain_step(mk(1, off + k - 1, 0, 0), prob.E, prob.W, [heads[k - 1]], o.z, o.hrun, masked=o.masked,
-                           revealed_at=o.revealed_at, cond_tok=o.cond_tok, protect_pos=o.protect_pos)
+                           revealed_at=o.revealed_at, cond_tok=o.cond_tok, protect_pos=o.protect_pos, x_tok=o.x_tok)
+        if rmode == 1:
+            ptok[k] = orc.token_prob(o.z, o.lse[1], o.x_tok)
         tok[k], conf[k], lse[k], gap[k], rem[k] = o.tok[1], o.conf[1], o.lse[1], o.gap[1], o.remasked[1]
         dpos[:, k], dtok[:, k] = o.draft_pos[:, 1], o.draft_tok[:, 1]
         snap(o)
     out = SimpleNamespace(z=o.z, hrun=o.hrun, tok=tok, conf=conf, lse=lse, gap=gap, remasked=rem, draft_pos=dpos,
                           draft_tok=dtok, masked=o.masked, revealed_at=o.revealed_at, cond_tok=o.cond_tok,
-                          protect_pos=o.protect_pos)
+                          protect_pos=o.protect_pos, x_tok=o.x_tok, ptok=ptok)
     return OracleRun(out, snaps)
 
 
@@ -188,6 +194,8 @@ def compare_chain(g: SimpleNamespace, z_g_rows: Optional[np.ndarray], hrun_g_row
                 diverged = True
                 break
             fragile = fragile or _fragile(o.conf[k, ro], rcfg.tau, rcfg.tau_remask)
+            if getattr(rcfg, "remask_mode", 0) == 1 and rcfg.tau_remask >= 0:
+                fragile = fragile or bool(np.any(np.abs(o.ptok[k, ro] - rcfg.tau_remask) < CONF_EXEMPT * rcfg.tau_remask))
             same = (g.draft_pos[b, k] == o.draft_pos[jj, k] and g.draft_tok[b, k] == o.draft_tok[jj, k]
                     and np.array_equal(g.remasked[k, rg], o.remasked[k, ro]))
             if not same:
@@ -198,7 +206,8 @@ def compare_chain(g: SimpleNamespace, z_g_rows: Optional[np.ndarray], hrun_g_row
                 break
         if not diverged:
             same = (np.array_equal(g.masked[rg], o.masked[ro]) and np.array_equal(g.revealed_at[rg], o.revealed_at[ro])
-                    and g.cond_tok[b] == o.cond_tok[jj] and g.protect_pos[b] == o.protect_pos[jj])
+                    and g.cond_tok[b] == o.cond_tok[jj] and g.protect_pos[b] == o.protect_pos[jj]
+                    and np.array_equal(g.x_tok[rg], o.x_tok[ro]))
             if not same:
                 assert fragile, (f"seq {b}: final masks differ: {g.masked[rg]} vs {o.masked[ro]}; "
                                  f"{g.revealed_at[rg]} vs {o.revealed_at[ro]}")

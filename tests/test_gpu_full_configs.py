@@ -26,7 +26,10 @@ def _run_full(cfg, rcfg, seqs, steps=1):
         rows = _sample_rows(cfg, seqs)
         z_o = z_d[torch.from_numpy(rows).cuda()].cpu().numpy().astype(np.float64)
         io = mrp.StepIO(cfg.B, cfg.L, cfg.K)
-        o_state = dict(masked=None, revealed_at=None, cond_tok=None, protect_pos=None)
+        o_state = dict(masked=None, revealed_at=None, cond_tok=None, protect_pos=None, x_tok=None)
+        x_out_d = torch.full((cfg.M,), -1, dtype=torch.int32, device="cuda")
+        n_masked_d = torch.empty((cfg.B,), dtype=torch.int32, device="cuda")
+        x_out_o = np.full(len(rows), -1, np.int32)
         all_stats = []
         for step in range(steps):
             h = mi.hidden(cfg, step=step)
@@ -41,10 +44,13 @@ def _run_full(cfg, rcfg, seqs, steps=1):
             print(f"\n[config {cfg.cid} step {step}: rows={cfg.M} sample={len(rows)}] {stats}", flush=True)
             if step + 1 < steps:
                 # between denoising steps the caller commits what stayed revealed; z stays resident
-                io.revealed_at[io.revealed_at >= 0] = -2
-                ra = o.out.revealed_at.copy(); ra[ra >= 0] = -2
+                prob.ctx.commit(cfg.B, io.x_tok, io.revealed_at, io.masked, x_out_d, n_masked_d)
+                x_out_o, ra, n_o = orc.commit(len(seqs), cfg.L, o.out.x_tok, o.out.revealed_at, o.out.masked, x_out_o)
+                if not stats["diverged"]:
+                    np.testing.assert_array_equal(x_out_d.cpu().numpy()[rows], x_out_o)
+                    np.testing.assert_array_equal(n_masked_d.cpu().numpy()[list(seqs)], n_o)
                 o_state = dict(masked=o.out.masked, revealed_at=ra, cond_tok=o.out.cond_tok,
-                               protect_pos=o.out.protect_pos)
+                               protect_pos=o.out.protect_pos, x_tok=o.out.x_tok)
                 z_o = o.out.z
                 if stats["diverged"]:
                     break   # an exempted decision changes the sequence's later inputs: stop comparing

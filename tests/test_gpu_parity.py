@@ -152,6 +152,7 @@ def test_teacher_forced_heads_and_resume():
             io = mrp.StepIO(cfg.B, cfg.L, 1)
             io.masked.copy_(torch.from_numpy(s.masked)); io.revealed_at.copy_(torch.from_numpy(s.revealed_at))
             io.cond_tok.copy_(torch.from_numpy(s.cond_tok)); io.protect_pos.copy_(torch.from_numpy(s.protect_pos))
+            io.x_tok.copy_(torch.from_numpy(s.x_tok))
             z_d = torch.from_numpy(s.z.astype(np.float32)).cuda()
             hrun_d = torch.from_numpy(s.hrun.astype(np.float32)).cuda()
             r1 = mrp.RevealCfg(tau=rcfg.tau, tau_remask=rcfg.tau_remask, fresh_block=0, state_offset=k - 1,
@@ -159,7 +160,7 @@ def test_teacher_forced_heads_and_resume():
             io, hrun_d = gpu_chain(prob, cfg.B, 1, z_d, None, r1, io=io, hrun_d=hrun_d, heads=prob.heads_d[k - 1:k])
             g = io_to_host(io)
             o1 = oracle_chain(prob, s.z, s.hrun, r1, 1, masked=s.masked, revealed_at=s.revealed_at,
-                              cond_tok=s.cond_tok, protect_pos=s.protect_pos, heads=prob.heads[k - 1:k])
+                              cond_tok=s.cond_tok, protect_pos=s.protect_pos, heads=prob.heads[k - 1:k], x_tok=s.x_tok)
             stats = compare_chain(g, z_d.cpu().numpy(), hrun_d.cpu().numpy(), o1.out, seqs, cfg.L, 1, r1)
             print(f"\n[teacher-forced head {k}] {stats}")
             np.testing.assert_array_equal(o1.out.tok[1], full.out.tok[k])

@@ -424,3 +424,104 @@ def test_chain_remask_and_reveal_control_flow():
     np.testing.assert_array_equal(out.masked.astype(bool), masked)
     np.testing.assert_array_equal(out.revealed_at, ra)
     assert n_rem > 0 and (out.revealed_at == 0).sum() > cfg.B     # both branches were exercised
+
+
+# ---- decode loop around the chain: recorded token, committed-token remask, commit, block decode ----
+
+def test_token_prob_against_library_softmax():
+    """softmax(z)[x_tok] via scipy; it never exceeds the top-1 probability and equals it at the argmax."""
+    from scipy.special import softmax
+    z = RNG.normal(0, 2, (7, 300))
+    tok, conf, lse = orc.reduce_rows(z)
+    x = RNG.integers(0, 300, 7).astype(np.int32)
+    x[2] = tok[2]; x[5] = -1
+    p = orc.token_prob(z, lse, x)
+    ref = softmax(z, axis=1)[np.arange(7), np.clip(x, 0, None)]
+    ref[5] = 0.0
+    np.testing.assert_allclose(p, ref, rtol=1e-12)
+    assert np.all(p <= conf * (1 + 1e-12))
+    np.testing.assert_allclose(p[2], conf[2], rtol=1e-12)
+
+
+def test_commit_bookkeeping():
+    B, L = 3, 5
+    M = B * L
+    ra = np.array([-2, -1, 0, 2, -1,   -1, -1, -1, -1, -1,   1, 0, -2, 3, 2], np.int8)
+    masked = (ra == -1).astype(np.uint8)
+    x_tok = np.arange(100, 100 + M, dtype=np.int32)
+    x_out0 = np.full(M, -1, np.int32); x_out0[[0, 12]] = 7          # committed in earlier steps
+    x_out, ra2, n = orc.commit(B, L, x_tok, ra, masked, x_out0)
+    new = ra >= 0
+    np.testing.assert_array_equal(x_out[new], x_tok[new])
+    np.testing.assert_array_equal(x_out[~new], x_out0[~new])         # earlier commits and masked rows untouched
+    np.testing.assert_array_equal(ra2, np.where(new, -2, ra))
+    np.testing.assert_array_equal(n, [2, 5, 0])
+
+
+def _decode_problem(B=4, L=8, V=512, K=2):
+    cfg = mi.straddling(mi.config(0, B=B, L=L, V=V, K=K))
+    W, E = mi.lm_head(cfg), mi.embedding(cfg)
+    heads = [mi.head_weights(cfg, k) for k in range(cfg.K)]
+
+    def backbone(step, x_out, masked):          # a stand-in backbone: fresh seeded logits / hidden states per step
+        return mi.logits0(cfg, step=step).astype(np.float64), val(mi.hidden(cfg, step=step))
+    return cfg, W, E, heads, backbone
+
+
+def test_decode_block_static_and_threshold_limits():
+    cfg, W, E, heads, backbone = _decode_problem()
+    L, K = cfg.L, cfg.K
+    # tau = 0: the backbone's own state reveals everything; one step, no head needed to finish
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, L, K, tau=0.0)
+    x, steps, hist = orc.decode_block(oc, E, W, heads, backbone)
+    assert steps == 1 and np.all(x >= 0)
+    np.testing.assert_array_equal(x, hist[0].tok[0])                  # state 0 argmax everywhere
+    # static decoding (tau >= 1): exactly r per state, K + 1 states per step
+    for r in (1, 2):
+        oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, L, K, tau=1.0, r_min=r)
+        x, steps, hist = orc.decode_block(oc, E, W, heads, backbone)
+        assert steps == -(-L // (r * (K + 1))) and np.all(x >= 0)
+        for t, out in enumerate(hist):
+            done_before = min(L, t * r * (K + 1))
+            np.testing.assert_array_equal((out.masked.reshape(cfg.B, L) == 0).sum(1),
+                                          np.full(cfg.B, min(L, done_before + r * (K + 1))))
+
+
+def test_decode_block_remask_progress_and_monotone_commit():
+    """Algorithm 4 (same threshold for reveal and remask) still commits at least one token per
+    sequence and step (the protected state-0 row), so a block of L finishes within L steps; a
+    committed token never changes afterwards."""
+    cfg, W, E, heads, backbone = _decode_problem()
+    for mode in (0, 1):
+        oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, tau=0.6, tau_remask=0.6, head_reveal=0,
+                          remask_mode=mode)
+        x, steps, hist = orc.decode_block(oc, E, W, heads, backbone)
+        assert steps <= cfg.L and np.all(x >= 0)
+        committed = np.zeros(cfg.M, bool)
+        n_prev = np.full(cfg.B, cfg.L)
+        for out in hist:
+            n_now = out.masked.reshape(cfg.B, cfg.L).sum(1)
+            assert np.all((n_now < n_prev) | (n_prev == 0))           # progress in every unfinished sequence
+            n_prev = n_now
+            newly = (out.revealed_at >= 0)
+            assert not np.any(newly & committed)
+            np.testing.assert_array_equal(x[newly], out.x_tok[newly])
+            committed |= newly
+
+
+def test_committed_token_remask_is_at_least_as_strict():
+    """p(revealed token) <= top-1 probability, so from identical inputs the committed-token rule
+    remasks a superset of what the top-1 rule remasks at the first head."""
+    cfg = mi.straddling(mi.config(0, B=6, L=8, V=512, K=1))
+    W, E = mi.lm_head(cfg), mi.embedding(cfg)
+    heads = [mi.head_weights(cfg, 0)]
+    z0, h = mi.logits0(cfg), val(mi.hidden(cfg))
+    outs = []
+    for mode in (0, 1):
+        oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, tau=0.3, tau_remask=0.8, remask_mode=mode)
+        outs.append(orc.chain_step(oc, E, W, heads, z0, h))
+    r0, r1 = outs[0].remasked[1].astype(bool), outs[1].remasked[1].astype(bool)
+    assert np.all(r0 <= r1) and r1.sum() > 0
+    # where the argmax did not move the two rules agree
+    same_tok = outs[1].tok[1] == outs[1].x_tok
+    np.testing.assert_array_equal(r0[same_tok], r1[same_tok])
