@@ -204,6 +204,16 @@ int mrp_verify_accept(mrp_ctx *ctx, void *stream, int B, int K, const float *ver
                       uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
                       int32_t *correction_tok /* [B] */);
 
+/* Joint verification of the K + 1 draft candidates (Figure 1 (d): candidate k
+ * embeds the first k drafts and all candidates are scored in one backbone
+ * pass).  verify is fp32 [B][K+1][L][V]; draft j is checked against candidate
+ * j's row at draft_pos[b][j].  Outputs as mrp_verify_accept; correction_tok[b]
+ * is candidate accept_len[b]'s argmax at the first rejected draft's position. */
+int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const float *verify,
+                            const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride,
+                            uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
+                            int32_t *correction_tok /* [B] */);
+
 /* Timing of the dominant kernel.  With profiling on, every LM-head kernel
  * launched by mrp_chain_step is bracketed by a pair of HIP events on the call's
  * stream (up to 4096 pairs between reads).  mrp_profile_read waits for the

@@ -139,6 +139,18 @@ def verify_accept(verify, draft_pos, draft_tok):
     return match, alen, corr
 
 
+def verify_accept_joint(verify, draft_pos, draft_tok):
+    """verify: float32 [B][K+1][L][V], candidate k holding the first k drafts."""
+    B, K1, L, V = verify.shape
+    K = draft_pos.shape[1]
+    assert K1 == K + 1
+    _chk(verify, np.float32); _chk(draft_pos, np.int32, (B, K)); _chk(draft_tok, np.int32, (B, K))
+    match = np.empty((B, K), np.uint8); alen = np.empty(B, np.int32); corr = np.empty(B, np.int32)
+    lib().orc_verify_accept_joint(B, L, V, K, _p(verify), _p(draft_pos), _p(draft_tok), _p(match), _p(alen),
+                                  _p(corr))
+    return match, alen, corr
+
+
 @dataclass
 class ChainOut:
     z: np.ndarray            # [M][V] float64, final logit state

@@ -28,6 +28,9 @@
  *   - commit: at the end of a denoising step the revealed tokens are written
  *       into the block and those positions stay unmasked in later steps
  *       (Algorithm 2: x_t <- reveal; Algorithm 4 returns R after remasking).
+ *   - joint verification: the K + 1 candidates C^0..C^K (candidate k holds the
+ *       first k drafts) are scored in one backbone pass; draft j is checked
+ *       against candidate j (Figure 1 (d)).
  *   - verify: a draft is accepted where the verifier's argmax equals the
  *       drafted token (Algorithm 3); the accepted length is the longest
  *       all-matching prefix of the draft list.
@@ -300,6 +303,38 @@ void orc_verify_accept(int B, int L, int V, int K, const float *verify, const in
             int vj = -1, ok = 0;
             if (pos >= 0) {
                 const float *r = verify + ((size_t)b * L + pos) * V;
+                float m = r[0];
+                vj = 0;
+                for (int v = 1; v < V; ++v) if (r[v] > m) { m = r[v]; vj = v; }
+                ok = (vj == draft_tok[(size_t)b * K + j]);
+            }
+            match[(size_t)b * K + j] = (uint8_t)ok;
+            if (open) {
+                if (ok) ++alen;
+                else { open = 0; correction_tok[b] = vj; }
+            }
+        }
+        accept_len[b] = alen;
+    }
+}
+
+/* Joint verification of the K + 1 draft candidates (Figure 1 (d)): candidate k carries the first
+ * k drafts, so draft j is checked against candidate j's logits, which were computed with drafts
+ * 0 .. j-1 in place and position draft_pos[j] still masked.  verify is [B][K+1][L][V].  The
+ * accepted length is the longest all-matching prefix; the correction token is candidate a's
+ * argmax at the first rejected draft's position (a = accepted length), -1 if all K are accepted
+ * or that draft is missing. */
+void orc_verify_accept_joint(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
+                             const int32_t *draft_tok, uint8_t *match, int32_t *accept_len,
+                             int32_t *correction_tok) {
+    for (int b = 0; b < B; ++b) {
+        int alen = 0, open = 1;
+        correction_tok[b] = -1;
+        for (int j = 0; j < K; ++j) {
+            const int pos = draft_pos[(size_t)b * K + j];
+            int vj = -1, ok = 0;
+            if (pos >= 0) {
+                const float *r = verify + (((size_t)b * (K + 1) + j) * L + pos) * V;
                 float m = r[0];
                 vj = 0;
                 for (int v = 1; v < V; ++v) if (r[v] > m) { m = r[v]; vj = v; }

@@ -10,7 +10,7 @@ from . import build as _build
 
 EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
-    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept",
+    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint",
     "mrp_profile_enable", "mrp_profile_read",
 ]
 
@@ -72,6 +72,8 @@ def load_library():
                                    C.POINTER(_StepIO)]
     lib.mrp_remask.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_float, C.c_void_p,
                                C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.mrp_verify_accept_joint.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                            C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.mrp_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                C.c_void_p]
     lib.mrp_verify_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -253,6 +255,13 @@ class MrpContext:
         rc = self.lib.mrp_verify_accept(self._h, _stream(), B, K, _ptr(verify), _ptr(draft_pos), _ptr(draft_tok),
                                         draft_stride, _ptr(match), _ptr(accept_len), _ptr(correction_tok))
         return self._check(rc, "mrp_verify_accept") if check else rc
+
+    def verify_accept_joint(self, B: int, K: int, verify, draft_pos, draft_tok, draft_stride: int, match,
+                            accept_len, correction_tok, check: bool = True) -> int:
+        rc = self.lib.mrp_verify_accept_joint(self._h, _stream(), B, K, _ptr(verify), _ptr(draft_pos),
+                                              _ptr(draft_tok), draft_stride, _ptr(match), _ptr(accept_len),
+                                              _ptr(correction_tok))
+        return self._check(rc, "mrp_verify_accept_joint") if check else rc
 
     def profile_enable(self, on: bool):
         self._check(self.lib.mrp_profile_enable(self._h, 1 if on else 0), "mrp_profile_enable")

@@ -426,7 +426,7 @@ int mrp_commit(mrp_ctx *c, void *stream, int B, const int32_t *x_tok, int8_t *re
     return MRP_OK;
 }
 
-int mrp_verify_accept(mrp_ctx *c, void *stream, int B, int K, const float *verify, const int32_t *draft_pos,
+static int verify_impl(mrp_ctx *c, void *stream, int B, int K, int joint, const float *verify, const int32_t *draft_pos,
                       const int32_t *draft_tok, int draft_stride, uint8_t *match, int32_t *accept_len,
                       int32_t *correction_tok) {
     if (!c) return MRP_ERR_NULL;
@@ -436,9 +436,23 @@ int mrp_verify_accept(mrp_ctx *c, void *stream, int B, int K, const float *verif
         return fail(c, MRP_ERR_SHAPE, "mrp_verify_accept: B=%d K=%d stride=%d out of range", B, K, draft_stride);
     if (c->dims.V % 4 == 0 && !aligned16(verify)) return fail(c, MRP_ERR_ALIGN, "verify must be 16-byte aligned");
     if (B == 0) return MRP_OK;
-    HIP_TRY(c, launch_verify(B, c->dims.block_len, c->dims.V, K, verify, draft_pos, draft_tok, draft_stride, c->vwm,
+    HIP_TRY(c, launch_verify(B, c->dims.block_len, c->dims.V, K, joint, verify, draft_pos, draft_tok, draft_stride, c->vwm,
                              c->vwi, match, accept_len, correction_tok, static_cast<hipStream_t>(stream)));
     return MRP_OK;
+}
+
+int mrp_verify_accept(mrp_ctx *c, void *stream, int B, int K, const float *verify, const int32_t *draft_pos,
+                      const int32_t *draft_tok, int draft_stride, uint8_t *match, int32_t *accept_len,
+                      int32_t *correction_tok) {
+    return verify_impl(c, stream, B, K, 0, verify, draft_pos, draft_tok, draft_stride, match, accept_len,
+                       correction_tok);
+}
+
+int mrp_verify_accept_joint(mrp_ctx *c, void *stream, int B, int K, const float *verify, const int32_t *draft_pos,
+                            const int32_t *draft_tok, int draft_stride, uint8_t *match, int32_t *accept_len,
+                            int32_t *correction_tok) {
+    return verify_impl(c, stream, B, K, 1, verify, draft_pos, draft_tok, draft_stride, match, accept_len,
+                       correction_tok);
 }
 
 }  // extern "C"

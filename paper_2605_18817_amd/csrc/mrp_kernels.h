@@ -180,7 +180,7 @@ hipError_t launch_commit(int B, int L, const int32_t *x_tok, int8_t *revealed_at
 hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_remask,
                          const int32_t *protect_pos, int8_t *revealed_at, uint8_t *masked,
                          uint8_t *remasked, hipStream_t st);
-hipError_t launch_verify(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
+hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *verify, const int32_t *draft_pos,
                          const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
                          int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
 int verify_chunks(int V);

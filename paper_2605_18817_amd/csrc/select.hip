@@ -267,7 +267,8 @@ __global__ __launch_bounds__(64) void remask_kernel(int B, int L, int state, con
 
 // argmax partial of one RT-wide chunk of the verifier row of draft (b, j)
 template <bool VEC4>
-__global__ __launch_bounds__(256) void verify_argmax_kernel(int L, int V, int K, const float *__restrict__ verify,
+__global__ __launch_bounds__(256) void verify_argmax_kernel(int L, int V, int K, int joint,
+                                                            const float *__restrict__ verify,
                                                             const int32_t *__restrict__ draft_pos, int draft_stride,
                                                             int nC, float *__restrict__ wm, int *__restrict__ wi) {
     __shared__ float sm[4], ss[4];
@@ -278,7 +279,9 @@ __global__ __launch_bounds__(256) void verify_argmax_kernel(int L, int V, int K,
     if (pos >= L) pos = -1;  // caller contract: pos < L; an invalid position counts as a missing draft
     Part p = part_identity();
     if (pos >= 0) {  // uniform over the workgroup
-        const float *row = verify + ((size_t)b * L + pos) * V;
+        // joint: [B][K+1][L][V], draft j reads candidate j; else one [B][L][V] tensor
+        const size_t blk = joint ? (size_t)b * (K + 1) + j : (size_t)b;
+        const float *row = verify + (blk * L + pos) * V;
         const int v0 = c * RT;
         if constexpr (VEC4) {
             float4 q[8];
@@ -372,15 +375,15 @@ hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_r
     return hipGetLastError();
 }
 
-hipError_t launch_verify(int B, int L, int V, int K, const float *verify, const int32_t *draft_pos,
+hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *verify, const int32_t *draft_pos,
                          const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
                          int32_t *accept_len, int32_t *correction_tok, hipStream_t st) {
     const int nC = verify_chunks(V);
     if (V % 4 == 0)
-        hipLaunchKernelGGL(verify_argmax_kernel<true>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, verify,
+        hipLaunchKernelGGL(verify_argmax_kernel<true>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, joint, verify,
                            draft_pos, draft_stride, nC, wm, wi);
     else
-        hipLaunchKernelGGL(verify_argmax_kernel<false>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, verify,
+        hipLaunchKernelGGL(verify_argmax_kernel<false>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, joint, verify,
                            draft_pos, draft_stride, nC, wm, wi);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

@@ -5,6 +5,7 @@ import numpy as np
 import pytest
 import torch
 
+import mrp_inputs as mi
 import oracle as orc
 import paper_2605_18817_amd as mrp
 
@@ -71,3 +72,31 @@ def test_remask_entry_point():
     assert ctx.remask(B + 1, 1, c_d, 0.5, None, ra_d, m_d, out, check=False) == -2
     assert ctx.remask(B, 1, None, 0.5, None, ra_d, m_d, out, check=False) == -1
     ctx.close()
+
+
+def test_joint_candidate_verification_exact():
+    """K + 1 candidate tensors, draft j checked against candidate j (bit-exact integers)."""
+    cfg = mi.config(0, B=9, L=16, V=4100)
+    K = 3
+    ctx = mrp.MrpContext(cfg.d, cfg.V, cfg.M, cfg.L)
+    try:
+        rng = np.random.default_rng(5)
+        ver = rng.normal(0, 2, (cfg.B, K + 1, cfg.L, cfg.V)).astype(np.float32)
+        dpos = rng.integers(-1, cfg.L, (cfg.B, K)).astype(np.int32)
+        dtok = rng.integers(0, cfg.V, (cfg.B, K)).astype(np.int32)
+        for b in range(cfg.B):
+            for j in range(K):
+                if dpos[b, j] >= 0 and rng.random() < 0.7:
+                    dtok[b, j] = int(np.argmax(ver[b, j, dpos[b, j]]))
+        want = orc.verify_accept_joint(ver, dpos, dtok)
+        match = torch.zeros((cfg.B, K), dtype=torch.uint8, device="cuda")
+        alen = torch.zeros(cfg.B, dtype=torch.int32, device="cuda"); corr = torch.zeros(cfg.B, dtype=torch.int32, device="cuda")
+        ctx.verify_accept_joint(cfg.B, K, torch.from_numpy(ver).cuda(), torch.from_numpy(dpos).cuda(),
+                                torch.from_numpy(dtok).cuda(), K, match, alen, corr)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(match.cpu().numpy(), want[0])
+        np.testing.assert_array_equal(alen.cpu().numpy(), want[1])
+        np.testing.assert_array_equal(corr.cpu().numpy(), want[2])
+        assert 0 < want[1].sum() < cfg.B * K
+    finally:
+        ctx.close()

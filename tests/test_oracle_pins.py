@@ -525,3 +525,32 @@ def test_committed_token_remask_is_at_least_as_strict():
     # where the argmax did not move the two rules agree
     same_tok = outs[1].tok[1] == outs[1].x_tok
     np.testing.assert_array_equal(r0[same_tok], r1[same_tok])
+
+
+def test_joint_candidate_verification_brute_force():
+    """Draft j is checked against candidate j; equals the single-tensor rule when all candidates
+    are the same tensor, and a brute-force longest matching prefix otherwise."""
+    B, L, K = 5, 4, 3
+    for V in (4, 8, 16):
+        ver = RNG.normal(0, 2, (B, K + 1, L, V)).astype(np.float32)
+        dpos = RNG.integers(-1, L, (B, K)).astype(np.int32)
+        dtok = RNG.integers(0, V, (B, K)).astype(np.int32)
+        # make about half of the drafts correct under their own candidate
+        for b in range(B):
+            for j in range(K):
+                if dpos[b, j] >= 0 and RNG.random() < 0.6:
+                    dtok[b, j] = int(np.argmax(ver[b, j, dpos[b, j]]))
+        match, alen, corr = orc.verify_accept_joint(ver, dpos, dtok)
+        for b in range(B):
+            ok = [dpos[b, j] >= 0 and int(np.argmax(ver[b, j, dpos[b, j]])) == dtok[b, j] for j in range(K)]
+            np.testing.assert_array_equal(match[b], ok)
+            a = 0
+            while a < K and ok[a]:
+                a += 1
+            assert alen[b] == a
+            want = -1 if a == K or dpos[b, a] < 0 else int(np.argmax(ver[b, a, dpos[b, a]]))
+            assert corr[b] == want
+        same = np.repeat(ver[:, :1], K + 1, axis=1).copy()
+        m1, a1, c1 = orc.verify_accept_joint(same, dpos, dtok)
+        m0, a0, c0 = orc.verify_accept(np.ascontiguousarray(same[:, 0]), dpos, dtok)
+        np.testing.assert_array_equal(m1, m0); np.testing.assert_array_equal(a1, a0); np.testing.assert_array_equal(c1, c0)
