@@ -151,6 +151,19 @@ def verify_accept_joint(verify, draft_pos, draft_tok):
     return match, alen, corr
 
 
+def kl_loss(teacher, student, row_mask=None, scale=1.0, want_grad=True):
+    """Equation 3 per row and its gradient w.r.t. the student logits.  teacher/student float32 [M][V];
+    returns (loss float64 [M], grad float64 [M][V] or None)."""
+    M, V = teacher.shape
+    _chk(teacher, np.float32); _chk(student, np.float32, (M, V))
+    if row_mask is not None:
+        _chk(row_mask, np.uint8, (M,))
+    loss = np.empty(M, np.float64)
+    grad = np.empty((M, V), np.float64) if want_grad else None
+    lib().orc_kl_loss(M, V, _p(teacher), _p(student), _p(row_mask), C.c_double(scale), _p(loss), _p(grad))
+    return loss, grad
+
+
 @dataclass
 class ChainOut:
     z: np.ndarray            # [M][V] float64, final logit state

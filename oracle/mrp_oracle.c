@@ -350,6 +350,41 @@ void orc_verify_accept_joint(int B, int L, int V, int K, const float *verify, co
     }
 }
 
+/* Training objective of a head (Section 3.3, Equation 3), written as its definition: for each
+ * row with row_mask != 0 (NULL: every row), p = softmax(teacher row) (the logits of denoising
+ * step t-1), q = softmax(student row) (l_t + delta_t),
+ *     loss[i] = scale * sum_v p_v (log p_v - log q_v),
+ * and, when grad is not NULL, its derivative with respect to the student logits,
+ *     grad[i][v] = scale * (q_v - p_v)
+ * (from d(-sum_v p_v log q_v)/ds_u = q_u - p_u with sum_v p_v = 1).  Rows outside the mask get
+ * loss 0 and gradient 0.  teacher/student are fp32 [M][V], read into fp64. */
+void orc_kl_loss(int M, int V, const float *teacher, const float *student, const uint8_t *row_mask,
+                 double scale, double *loss, double *grad) {
+    double *lp = (double *)malloc(sizeof(double) * V), *lq = (double *)malloc(sizeof(double) * V);
+    for (int i = 0; i < M; ++i) {
+        const float *t = teacher + (size_t)i * V, *s = student + (size_t)i * V;
+        if (row_mask && !row_mask[i]) {
+            loss[i] = 0.0;
+            if (grad) for (int v = 0; v < V; ++v) grad[(size_t)i * V + v] = 0.0;
+            continue;
+        }
+        double mt = t[0], ms = s[0];
+        for (int v = 1; v < V; ++v) { if (t[v] > mt) mt = t[v]; if (s[v] > ms) ms = s[v]; }
+        double st = 0.0, ss = 0.0;
+        for (int v = 0; v < V; ++v) { st += exp((double)t[v] - mt); ss += exp((double)s[v] - ms); }
+        const double lt = mt + log(st), ls = ms + log(ss);
+        double kl = 0.0;
+        for (int v = 0; v < V; ++v) {
+            lp[v] = (double)t[v] - lt;
+            lq[v] = (double)s[v] - ls;
+            kl += exp(lp[v]) * (lp[v] - lq[v]);
+        }
+        loss[i] = scale * kl;
+        if (grad) for (int v = 0; v < V; ++v) grad[(size_t)i * V + v] = scale * (exp(lq[v]) - exp(lp[v]));
+    }
+    free(lp); free(lq);
+}
+
 /* One denoising step's chain.
  *   z       [M][V] fp64 in/out         hrun [M][d] fp64 in/out
  *   heads   K triples of bf16 arrays   (W1[k], W2[k], gamma[k])

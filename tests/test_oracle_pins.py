@@ -554,3 +554,77 @@ def test_joint_candidate_verification_brute_force():
         m1, a1, c1 = orc.verify_accept_joint(same, dpos, dtok)
         m0, a0, c0 = orc.verify_accept(np.ascontiguousarray(same[:, 0]), dpos, dtok)
         np.testing.assert_array_equal(m1, m0); np.testing.assert_array_equal(a1, a0); np.testing.assert_array_equal(c1, c0)
+
+
+# ---------------------------------------------------------------------------------------------
+# Training objective (Section 3.3, Equation 3)
+def test_kl_loss_against_library_and_closed_forms():
+    """KL(softmax(teacher) || softmax(student)) per row against scipy's softmax + rel_entr, a
+    two-class closed form, shift invariance, and the zero at student = teacher + const."""
+    from scipy.special import rel_entr, softmax
+    M, V = 7, 333
+    t = RNG.normal(0, 2, (M, V)).astype(np.float32)
+    s = (t + RNG.normal(0, 1, (M, V))).astype(np.float32)
+    loss, grad = orc.kl_loss(t, s)
+    want = rel_entr(softmax(t.astype(np.float64), axis=1), softmax(s.astype(np.float64), axis=1)).sum(1)
+    np.testing.assert_allclose(loss, want, rtol=1e-10, atol=1e-13)
+    assert np.all(loss > 0)
+    # an asymmetric pair: swapping the arguments gives a different number (catches a transposed operand)
+    loss_sw, _ = orc.kl_loss(s, t)
+    assert np.all(np.abs(loss_sw - loss) > 1e-6)
+    # two classes: p = sigmoid(a), q = sigmoid(b)
+    a, b = 1.25, -0.5
+    two_t = np.array([[a, 0.0]], np.float32); two_s = np.array([[b, 0.0]], np.float32)
+    p, q = 1 / (1 + np.exp(-a)), 1 / (1 + np.exp(-b))
+    l2, g2 = orc.kl_loss(two_t, two_s)
+    np.testing.assert_allclose(l2[0], p * np.log(p / q) + (1 - p) * np.log((1 - p) / (1 - q)), rtol=1e-12)
+    np.testing.assert_allclose(g2[0], [q - p, p - q], rtol=1e-12)
+    # softmax is shift invariant: a per-row constant on either side changes nothing; equal up to a constant -> 0
+    shift = (s + np.float32(3.0)).astype(np.float32)
+    l3, g3 = orc.kl_loss(t, shift)
+    np.testing.assert_allclose(l3, loss, rtol=1e-5, atol=1e-7)      # (fp32 input rounding of s + 3)
+    l0, g0 = orc.kl_loss(t, (t + np.float32(2.0)).astype(np.float32))
+    np.testing.assert_allclose(l0, 0.0, atol=1e-6)
+    np.testing.assert_allclose(g0, 0.0, atol=1e-6)
+    # scale multiplies both outputs
+    ls, gs = orc.kl_loss(t, s, scale=0.125)
+    np.testing.assert_allclose(ls, 0.125 * loss, rtol=1e-14)
+    np.testing.assert_allclose(gs, 0.125 * grad, rtol=1e-14)
+
+
+def test_kl_loss_gradient_finite_differences_and_mask():
+    """grad is d loss_i / d student[i][v]: central differences (student perturbed in fp32-exact
+    steps of 2^-7), rows of the gradient sum to zero, unmasked rows contribute nothing."""
+    M, V = 4, 41
+    t = RNG.normal(0, 2, (M, V)).astype(np.float32)
+    s = np.round((t + RNG.normal(0, 1, (M, V))) * 64) / 64          # on a 2^-6 grid: +-2^-7 is exact in fp32
+    s = s.astype(np.float32)
+    mask = np.array([1, 0, 1, 1], np.uint8)
+    loss, grad = orc.kl_loss(t, s, mask, scale=0.5)
+    assert loss[1] == 0.0 and np.all(grad[1] == 0.0)
+    np.testing.assert_allclose(grad.sum(1), 0.0, atol=1e-14)
+    full, _ = orc.kl_loss(t, s, None, scale=0.5)
+    np.testing.assert_array_equal(loss[mask == 1], full[mask == 1])
+    eps = 2.0 ** -7
+    for i in (0, 2, 3):
+        for v in range(V):
+            sp, sm = s.copy(), s.copy()
+            sp[i, v] += np.float32(eps); sm[i, v] -= np.float32(eps)
+            lp, _ = orc.kl_loss(t, sp, mask, scale=0.5, want_grad=False)
+            lm, _ = orc.kl_loss(t, sm, mask, scale=0.5, want_grad=False)
+            fd = (lp[i] - lm[i]) / (2 * eps)
+            assert abs(fd - grad[i, v]) < 2e-5, (i, v, fd, grad[i, v])   # O(eps^2) truncation
+            assert lp[1] == 0.0
+
+
+def test_kl_loss_one_hot_teacher_is_cross_entropy():
+    """A teacher with one dominant logit makes Equation 3 the cross entropy -log q[target]."""
+    from scipy.special import log_softmax
+    M, V = 3, 64
+    s = RNG.normal(0, 2, (M, V)).astype(np.float32)
+    tgt = RNG.integers(0, V, M)
+    t = np.full((M, V), -80.0, np.float32)
+    t[np.arange(M), tgt] = 80.0
+    loss, grad = orc.kl_loss(t, s)
+    ce = -log_softmax(s.astype(np.float64), axis=1)[np.arange(M), tgt]
+    np.testing.assert_allclose(loss, ce, rtol=1e-12)
