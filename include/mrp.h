@@ -214,6 +214,18 @@ int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const floa
                             uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
                             int32_t *correction_tok /* [B] */);
 
+/* Training-side objective of the head (Section 3.3, Equation 3), forward and
+ * gradient: for every row i with row_mask[i] != 0 (NULL = all rows),
+ *   loss_rows[i] = scale * KL( softmax(teacher[i]) || softmax(student[i]) ),
+ *   grad[i][v]   = scale * ( softmax(student[i])[v] - softmax(teacher[i])[v] )
+ * (the derivative of loss_rows[i] with respect to student[i][v], i.e. to the
+ * predicted residual delta), and 0 for the other rows.  teacher = l_{t-1},
+ * student = l_t + delta_t, both fp32 [M][V] device; loss_rows fp32 [M];
+ * grad fp32 [M][V] or NULL (forward only).  M <= max_rows.  No softmax is
+ * materialised: one pass over both tensors for the loss, one more for grad. */
+int mrp_kl_loss(mrp_ctx *ctx, void *stream, int M, const float *teacher, const float *student,
+                const uint8_t *row_mask, float scale, float *loss_rows, float *grad);
+
 /* Timing of the dominant kernel.  With profiling on, every LM-head kernel
  * launched by mrp_chain_step is bracketed by a pair of HIP events on the call's
  * stream (up to 4096 pairs between reads).  mrp_profile_read waits for the

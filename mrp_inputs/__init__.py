@@ -15,6 +15,7 @@ SDAR-1.7B / SDAR-8B backbones, Section 4.1 "Models"):
 * hidden states ``h``: bf16 [M, d], N(0, 1).
 * prior logit state ``z0``: fp32 [M, V], N(0, 2); optionally a fraction of the
   rows receives one additive spike at a uniformly drawn vocabulary index.
+* stand-in residual ``delta`` for the training objective: fp32 [M, V], N(0, 0.5).
 * verify logits: fp32 [B, L, V], N(0, 2); a +8 boost is *added by the caller*
   at the drafted (position, token) pairs selected by ``verify_boost_mask``.
 
@@ -36,7 +37,7 @@ import numpy as np
 SEED_BASE = 0x4D5250  # "MRP"
 
 # tensor ids (part of the seed)
-T_WLM, T_E, T_W1, T_W2, T_H, T_Z, T_SPIKE, T_VERIFY, T_BOOST = range(9)
+T_WLM, T_E, T_W1, T_W2, T_H, T_Z, T_SPIKE, T_VERIFY, T_BOOST, T_DELTA = range(10)
 
 WEIGHT_CHUNK_ROWS = 4096
 
@@ -211,6 +212,20 @@ def logits0(cfg: Config, seqs: Optional[Iterable[int]] = None, out: Optional[np.
             for r in range(cfg.L):
                 if hit[r]:
                     blk[r, idx[r]] += hgt[r]
+
+    _pmap(one, range(len(s)))
+    return out
+
+
+def residual(cfg: Config, seqs: Optional[Iterable[int]] = None, step: int = 0) -> np.ndarray:
+    """Stand-in for a head's predicted logit residual ``delta_t``: fp32 [len(seqs)*L, V], N(0, 0.5)."""
+    s = _seqs(cfg, seqs)
+    out = np.empty((len(s) * cfg.L, cfg.V), dtype=np.float32)
+
+    def one(j):
+        blk = out[j * cfg.L:(j + 1) * cfg.L]
+        _rng(cfg.cid, T_DELTA, s[j], step).standard_normal(out=blk, dtype=np.float32)
+        blk *= np.float32(0.5)
 
     _pmap(one, range(len(s)))
     return out

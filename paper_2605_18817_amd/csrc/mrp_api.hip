@@ -30,6 +30,8 @@ struct mrp_ctx {
     int *pi;
     float *vwm;
     int *vwi;
+    float *kl_part, *kl_lse;   // KL loss: 5 partial arrays [max_rows * tiles], row log-sum-exps [2][max_rows]
+    size_t kl_stride;
     char err[512];
     bool prof_on;
     std::vector<hipEvent_t> ev;  // pairs
@@ -48,7 +50,8 @@ struct Layout {
     int nT_max;
     size_t part_rows;
     int maxB;
-    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, total;
+    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, off_klp, off_kll, total;
+    size_t kl_stride;
 };
 
 bool dims_ok(const mrp_dims *d) {
@@ -82,6 +85,9 @@ Layout make_layout(const mrp_dims *dm, int nCU) {
     const size_t vw = (size_t)l.maxB * MRP_MAX_HEADS * verify_chunks(dm->V);
     l.off_vwm = take(vw * 4);
     l.off_vwi = take(vw * 4);
+    l.kl_stride = (size_t)dm->max_rows * kl_tiles(dm->V);
+    l.off_klp = take(5 * l.kl_stride * 4);
+    l.off_kll = take((size_t)2 * dm->max_rows * 4);
     l.total = o;
     return l;
 }
@@ -166,6 +172,9 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     c->pi = reinterpret_cast<int *>(c->ws + l.off_pi);
     c->vwm = reinterpret_cast<float *>(c->ws + l.off_vwm);
     c->vwi = reinterpret_cast<int *>(c->ws + l.off_vwi);
+    c->kl_part = reinterpret_cast<float *>(c->ws + l.off_klp);
+    c->kl_lse = reinterpret_cast<float *>(c->ws + l.off_kll);
+    c->kl_stride = l.kl_stride;
     *out = c;
     return MRP_OK;
 }
@@ -192,6 +201,19 @@ int mrp_pack_weight(void *stream, const void *src, int rows, int cols, void *dst
     hipError_t e = launch_pack_weight(static_cast<const uint16_t *>(src), rows, cols, static_cast<uint4 *>(dst),
                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MRP_OK : MRP_ERR_HIP;
+}
+
+int mrp_kl_loss(mrp_ctx *c, void *stream, int M, const float *teacher, const float *student, const uint8_t *row_mask,
+                float scale, float *loss_rows, float *grad) {
+    if (!c) return MRP_ERR_NULL;
+    if (!teacher || !student || !loss_rows) return fail(c, MRP_ERR_NULL, "mrp_kl_loss: NULL pointer");
+    if (M < 0 || M > c->dims.max_rows) return fail(c, MRP_ERR_WORKSPACE, "mrp_kl_loss: M=%d exceeds max_rows", M);
+    if (c->dims.V % 4 == 0 && (!aligned16(teacher) || !aligned16(student) || (grad && !aligned16(grad))))
+        return fail(c, MRP_ERR_ALIGN, "mrp_kl_loss: tensors must be 16-byte aligned");
+    if (M == 0) return MRP_OK;
+    HIP_TRY(c, launch_kl_loss(M, c->dims.V, teacher, student, row_mask, scale, c->kl_part, c->kl_stride, c->kl_lse,
+                              loss_rows, grad, static_cast<hipStream_t>(stream)));
+    return MRP_OK;
 }
 
 int mrp_profile_enable(mrp_ctx *c, int on) {

@@ -185,4 +185,9 @@ hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *ver
                          int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
 int verify_chunks(int V);
 
+int kl_tiles(int V);
+hipError_t launch_kl_loss(int M, int V, const float *teacher, const float *student, const uint8_t *mask, float scale,
+                          float *part, size_t part_stride, float *lse, float *loss_rows, float *grad,
+                          hipStream_t st);
+
 }  // namespace mrp
