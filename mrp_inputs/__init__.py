@@ -16,6 +16,8 @@ SDAR-1.7B / SDAR-8B backbones, Section 4.1 "Models"):
 * prior logit state ``z0``: fp32 [M, V], N(0, 2); optionally a fraction of the
   rows receives one additive spike at a uniformly drawn vocabulary index.
 * stand-in residual ``delta`` for the training objective: fp32 [M, V], N(0, 0.5).
+* block states for the residual-magnitude measurement: ``X^(0)`` ~ N(0, 2), then independent
+  N(0, 0.4) increments per state (a random walk), fp32 [S, N] per block, optionally rounded to bf16.
 * verify logits: fp32 [B, L, V], N(0, 2); a +8 boost is *added by the caller*
   at the drafted (position, token) pairs selected by ``verify_boost_mask``.
 
@@ -37,7 +39,7 @@ import numpy as np
 SEED_BASE = 0x4D5250  # "MRP"
 
 # tensor ids (part of the seed)
-T_WLM, T_E, T_W1, T_W2, T_H, T_Z, T_SPIKE, T_VERIFY, T_BOOST, T_DELTA = range(10)
+T_WLM, T_E, T_W1, T_W2, T_H, T_Z, T_SPIKE, T_VERIFY, T_BOOST, T_DELTA, T_STATES = range(11)
 
 WEIGHT_CHUNK_ROWS = 4096
 
@@ -229,6 +231,20 @@ def residual(cfg: Config, seqs: Optional[Iterable[int]] = None, step: int = 0) -
 
     _pmap(one, range(len(s)))
     return out
+
+
+def block_states(cfg_id: int, block: int, S: int, N: int, bf16: bool = False, base_std: float = 2.0,
+                 step_std: float = 0.4) -> np.ndarray:
+    """Stand-in for the S states a backbone tensor goes through while one block is decoded:
+    state 0 ~ N(0, base_std), each later state the previous one plus fresh N(0, step_std) noise.
+    fp32 [S, N], or bf16 bits [S, N] (each state rounded after the sum)."""
+    g = _rng(cfg_id, T_STATES, block)
+    out = np.empty((S, N), dtype=np.float32)
+    g.standard_normal(out=out, dtype=np.float32)
+    out[0] *= np.float32(base_std)
+    out[1:] *= np.float32(step_std)
+    np.cumsum(out, axis=0, out=out)
+    return f32_to_bf16_bits(out) if bf16 else out
 
 
 def verify_logits(cfg: Config, seqs: Optional[Iterable[int]] = None) -> np.ndarray:

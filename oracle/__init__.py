@@ -164,6 +164,16 @@ def kl_loss(teacher, student, row_mask=None, scale=1.0, want_grad=True):
     return loss, grad
 
 
+def residual_rms(X):
+    """Appendix B magnitudes.  X float64 [n_blocks][S][N]; returns (rms_pair [n_blocks][S][S], rms_delta [S])
+    with rms_delta[0] the reference line and rms_delta[r] the mean RMS of the r-step residuals."""
+    nb, S, N = X.shape
+    _chk(X, np.float64)
+    pair = np.empty((nb, S, S), np.float64); delta = np.empty(S, np.float64)
+    lib().orc_residual_rms(nb, S, C.c_long(N), _p(X), _p(pair), _p(delta))
+    return pair, delta
+
+
 @dataclass
 class ChainOut:
     z: np.ndarray            # [M][V] float64, final logit state

@@ -385,6 +385,33 @@ void orc_kl_loss(int M, int V, const float *teacher, const float *student, const
     free(lp); free(lq);
 }
 
+/* Residual-magnitude measurement (Appendix B, the protocol behind Figure 2).  X holds, for each
+ * of n_blocks decoded blocks, the S = block + 1 states X^(0..S-1) of one tensor (logits or hidden
+ * states of the block's positions), N entries each, already in fp64.  With
+ *     ||Y||_RMS = sqrt( (1/N) sum_i Y_i^2 ),
+ *   rms_pair[b][t][u], u > t :  || X^(u) - X^(t) ||_RMS   (the residual delta_{t,r}, r = u - t)
+ *   rms_pair[b][s][s]        :  || X^(s) ||_RMS            (entries below the diagonal: 0)
+ *   rms_delta[r], r >= 1     :  mean of rms_pair[b][t][t+r] over every block b and t = 0 .. S-1-r
+ *   rms_delta[0]             :  the reference line: mean of rms_pair[b][s][s] over b and s = 1 .. S-1 */
+void orc_residual_rms(int n_blocks, int S, long N, const double *X, double *rms_pair, double *rms_delta) {
+    for (int b = 0; b < n_blocks; ++b)
+        for (int t = 0; t < S; ++t)
+            for (int u = 0; u < S; ++u) {
+                const double *xt = X + ((size_t)b * S + t) * N, *xu = X + ((size_t)b * S + u) * N;
+                double acc = 0.0;
+                if (u == t) for (long i = 0; i < N; ++i) acc += xt[i] * xt[i];
+                else if (u > t) for (long i = 0; i < N; ++i) { const double dlt = xu[i] - xt[i]; acc += dlt * dlt; }
+                rms_pair[((size_t)b * S + t) * S + u] = (u >= t) ? sqrt(acc / (double)N) : 0.0;
+            }
+    for (int r = 0; r < S; ++r) {
+        double sum = 0.0;
+        long cnt = 0;
+        for (int b = 0; b < n_blocks; ++b)
+            for (int t = (r == 0 ? 1 : 0); t + r < S; ++t) { sum += rms_pair[((size_t)b * S + t) * S + t + r]; ++cnt; }
+        rms_delta[r] = cnt ? sum / (double)cnt : 0.0;
+    }
+}
+
 /* One denoising step's chain.
  *   z       [M][V] fp64 in/out         hrun [M][d] fp64 in/out
  *   heads   K triples of bf16 arrays   (W1[k], W2[k], gamma[k])

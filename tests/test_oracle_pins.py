@@ -628,3 +628,56 @@ def test_kl_loss_one_hot_teacher_is_cross_entropy():
     loss, grad = orc.kl_loss(t, s)
     ce = -log_softmax(s.astype(np.float64), axis=1)[np.arange(M), tgt]
     np.testing.assert_allclose(loss, ce, rtol=1e-12)
+
+
+# ---------------------------------------------------------------------------------------------
+# Residual-magnitude measurement (Appendix B)
+def test_residual_rms_hand_example_and_closed_forms():
+    """A 3-state, 2-entry example worked by hand (3-4-5 triangles), a linear ramp
+    X^(s) = s c whose r-step residual has RMS r |c| exactly, and numpy's vector norm."""
+    X = np.array([[[0.0, 0.0], [3.0, 4.0], [6.0, 8.0]]])
+    pair, delta = orc.residual_rms(X)
+    s = np.sqrt(12.5)                                     # ||(3,4)||_RMS = sqrt(25/2)
+    np.testing.assert_allclose(pair[0], [[0, s, 2 * s], [0, s, s], [0, 0, 2 * s]], rtol=1e-15)
+    np.testing.assert_allclose(delta, [1.5 * s, s, 2 * s], rtol=1e-15)   # reference over s = 1, 2 only
+    # ramp, two blocks with different slopes: mean over blocks of r |c|
+    S, N = 6, 37
+    c = RNG.normal(0, 1, (2, 1, N))
+    ramp = np.ascontiguousarray(np.arange(S)[None, :, None] * c + 5.0)
+    pair, delta = orc.residual_rms(ramp)
+    crms = np.sqrt((c ** 2).mean(axis=(1, 2)))
+    for r in range(1, S):
+        np.testing.assert_allclose(delta[r], r * crms.mean(), rtol=1e-12)
+        for t in range(S - r):
+            np.testing.assert_allclose(pair[:, t, t + r], r * crms, rtol=1e-12)
+    # the residual ignores a common offset, the reference line does not
+    pair2, delta2 = orc.residual_rms(np.ascontiguousarray(ramp + 100.0))
+    np.testing.assert_allclose(delta2[1:], delta[1:], rtol=1e-9)
+    assert delta2[0] > delta[0] + 90
+    # library norm on random states; order of subtraction must not matter, the pairing must
+    X = RNG.normal(0, 2, (3, 5, 101))
+    pair, delta = orc.residual_rms(X)
+    for b in range(3):
+        for t in range(5):
+            for u in range(t, 5):
+                want = np.linalg.norm(X[b, u] - X[b, t] if u > t else X[b, t]) / np.sqrt(101)
+                np.testing.assert_allclose(pair[b, t, u], want, rtol=1e-13)
+    np.testing.assert_allclose(delta[2], np.mean([pair[b, t, t + 2] for b in range(3) for t in range(3)]), rtol=1e-14)
+    np.testing.assert_allclose(delta[0], np.mean([pair[b, s_, s_] for b in range(3) for s_ in range(1, 5)]), rtol=1e-14)
+
+
+def test_residual_rms_random_walk_statistics_and_bf16_range():
+    """The seeded stand-in states are a random walk with step deviation 0.4: the r-step residual
+    has RMS 0.4 sqrt(r) and state s has RMS sqrt(4 + 0.16 s) up to sampling noise; differences far
+    below a bf16 ulp of the states' sum of squares survive (the reason the paper computes in fp64)."""
+    S, N = 17, 20000
+    X = np.stack([mi.block_states(0, b, S, N) for b in range(2)]).astype(np.float64)
+    pair, delta = orc.residual_rms(X)
+    for r in range(1, S):
+        assert abs(delta[r] / (0.4 * np.sqrt(r)) - 1) < 0.02, (r, delta[r])
+    want_ref = np.mean([np.sqrt(4 + 0.16 * s) for s in range(1, S)])
+    assert abs(delta[0] / want_ref - 1) < 0.02
+    assert delta[1] < 0.25 * delta[0]                       # the magnitude gap the figure shows
+    tiny = np.zeros((1, 2, 8)); tiny[0, 0, :] = 1.0; tiny[0, 1, :] = 1.0 + 2.0 ** -7
+    pair, delta = orc.residual_rms(tiny)
+    np.testing.assert_allclose(delta[1], 2.0 ** -7, rtol=1e-15)
