@@ -226,6 +226,23 @@ int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const floa
 int mrp_kl_loss(mrp_ctx *ctx, void *stream, int M, const float *teacher, const float *student,
                 const uint8_t *row_mask, float scale, float *loss_rows, float *grad);
 
+/* Residual-magnitude measurement (Appendix B, the protocol behind Figure 2).
+ * X: device, [n_blocks][S][N], fp32 (dtype MRP_DTYPE_F32) or bf16 (MRP_DTYPE_BF16):
+ * for each decoded block the S = block length + 1 states of one backbone
+ * tensor restricted to the block (logits: N = L*V; hidden states: N = L*d),
+ * state s having s revealed positions.  With ||Y||_RMS = sqrt(sum Y_i^2 / N),
+ * all sums in fp64:
+ *   rms_pair  [n_blocks][S][S] (device, fp64):  [b][t][u] = ||X^(u) - X^(t)||_RMS
+ *             for u > t, ||X^(s)||_RMS on the diagonal, 0 below it;
+ *   rms_delta [S] (device, fp64): [r] for r >= 1 = mean of rms_pair[b][t][t+r]
+ *             over all blocks and t = 0 .. S-1-r; [0] = the reference line, the
+ *             mean of the diagonal over all blocks and s = 1 .. S-1.
+ * S must be 3, 5, 9 or 17; n_blocks <= 4096; every state is read once. */
+#define MRP_DTYPE_F32 0
+#define MRP_DTYPE_BF16 1
+int mrp_residual_rms(mrp_ctx *ctx, void *stream, int n_blocks, int S, long N, const void *X, int dtype,
+                     double *rms_pair, double *rms_delta);
+
 /* Timing of the dominant kernel.  With profiling on, every LM-head kernel
  * launched by mrp_chain_step is bracketed by a pair of HIP events on the call's
  * stream (up to 4096 pairs between reads).  mrp_profile_read waits for the

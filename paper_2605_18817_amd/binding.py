@@ -10,7 +10,7 @@ from . import build as _build
 
 EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
-    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss",
+    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms",
     "mrp_profile_enable", "mrp_profile_read",
 ]
 
@@ -76,6 +76,8 @@ def load_library():
                                             C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.mrp_kl_loss.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_float,
                                 C.c_void_p, C.c_void_p]
+    lib.mrp_residual_rms.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_void_p, C.c_int,
+                                     C.c_void_p, C.c_void_p]
     lib.mrp_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                C.c_void_p]
     lib.mrp_verify_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -270,6 +272,12 @@ class MrpContext:
         rc = self.lib.mrp_kl_loss(self._h, _stream(), M, _ptr(teacher), _ptr(student), _ptr(row_mask), scale,
                                   _ptr(loss_rows), _ptr(grad))
         return self._check(rc, "mrp_kl_loss") if check else rc
+
+    def residual_rms(self, n_blocks: int, S: int, N: int, X, bf16: bool, rms_pair, rms_delta,
+                     check: bool = True) -> int:
+        rc = self.lib.mrp_residual_rms(self._h, _stream(), n_blocks, S, N, _ptr(X), 1 if bf16 else 0,
+                                       _ptr(rms_pair), _ptr(rms_delta))
+        return self._check(rc, "mrp_residual_rms") if check else rc
 
     def profile_enable(self, on: bool):
         self._check(self.lib.mrp_profile_enable(self._h, 1 if on else 0), "mrp_profile_enable")

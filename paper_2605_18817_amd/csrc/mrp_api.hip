@@ -32,6 +32,7 @@ struct mrp_ctx {
     int *vwi;
     float *kl_part, *kl_lse;   // KL loss: 5 partial arrays [max_rows * tiles], row log-sum-exps [2][max_rows]
     size_t kl_stride;
+    double *rms_part;          // residual magnitudes: per-workgroup sums of squares
     char err[512];
     bool prof_on;
     std::vector<hipEvent_t> ev;  // pairs
@@ -50,7 +51,7 @@ struct Layout {
     int nT_max;
     size_t part_rows;
     int maxB;
-    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, off_klp, off_kll, total;
+    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, off_klp, off_kll, off_rms, total;
     size_t kl_stride;
 };
 
@@ -88,6 +89,7 @@ Layout make_layout(const mrp_dims *dm, int nCU) {
     l.kl_stride = (size_t)dm->max_rows * kl_tiles(dm->V);
     l.off_klp = take(5 * l.kl_stride * 4);
     l.off_kll = take((size_t)2 * dm->max_rows * 4);
+    l.off_rms = take(residual_rms_part_bytes());
     l.total = o;
     return l;
 }
@@ -175,6 +177,7 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     c->kl_part = reinterpret_cast<float *>(c->ws + l.off_klp);
     c->kl_lse = reinterpret_cast<float *>(c->ws + l.off_kll);
     c->kl_stride = l.kl_stride;
+    c->rms_part = reinterpret_cast<double *>(c->ws + l.off_rms);
     *out = c;
     return MRP_OK;
 }
@@ -213,6 +216,26 @@ int mrp_kl_loss(mrp_ctx *c, void *stream, int M, const float *teacher, const flo
     if (M == 0) return MRP_OK;
     HIP_TRY(c, launch_kl_loss(M, c->dims.V, teacher, student, row_mask, scale, c->kl_part, c->kl_stride, c->kl_lse,
                               loss_rows, grad, static_cast<hipStream_t>(stream)));
+    return MRP_OK;
+}
+
+int mrp_residual_rms(mrp_ctx *c, void *stream, int n_blocks, int S, long N, const void *X, int dtype,
+                     double *rms_pair, double *rms_delta) {
+    if (!c) return MRP_ERR_NULL;
+    if (!X || !rms_pair || !rms_delta) return fail(c, MRP_ERR_NULL, "mrp_residual_rms: NULL pointer");
+    if (!residual_rms_supported(S))
+        return fail(c, MRP_ERR_SHAPE, "mrp_residual_rms: S=%d states (block + 1) must be 3, 5, 9 or 17", S);
+    if (dtype != MRP_DTYPE_F32 && dtype != MRP_DTYPE_BF16)
+        return fail(c, MRP_ERR_SHAPE, "mrp_residual_rms: dtype %d is neither fp32 nor bf16", dtype);
+    if (n_blocks < 0 || N < 1 || n_blocks > residual_rms_max_blocks())
+        return fail(c, MRP_ERR_SHAPE, "mrp_residual_rms: n_blocks=%d (max %d), N=%ld", n_blocks,
+                    residual_rms_max_blocks(), N);
+    if ((reinterpret_cast<uintptr_t>(X) & (dtype == MRP_DTYPE_F32 ? 3u : 1u)) ||
+        (reinterpret_cast<uintptr_t>(rms_pair) & 7u) || (reinterpret_cast<uintptr_t>(rms_delta) & 7u))
+        return fail(c, MRP_ERR_ALIGN, "mrp_residual_rms: pointers must be aligned to their element size");
+    if (n_blocks == 0) return MRP_OK;
+    HIP_TRY(c, launch_residual_rms(n_blocks, S, N, X, dtype == MRP_DTYPE_BF16, c->rms_part, rms_pair, rms_delta,
+                                   static_cast<hipStream_t>(stream)));
     return MRP_OK;
 }
 

@@ -185,6 +185,12 @@ hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *ver
                          int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
 int verify_chunks(int V);
 
+size_t residual_rms_part_bytes();
+int residual_rms_max_blocks();
+bool residual_rms_supported(int S);
+hipError_t launch_residual_rms(int n_blocks, int S, long N, const void *X, bool bf16, double *part,
+                               double *rms_pair, double *rms_delta, hipStream_t st);
+
 int kl_tiles(int V);
 hipError_t launch_kl_loss(int M, int V, const float *teacher, const float *student, const uint8_t *mask, float scale,
                           float *part, size_t part_stride, float *lse, float *loss_rows, float *grad,
