@@ -18,6 +18,9 @@ SDAR-1.7B / SDAR-8B backbones, Section 4.1 "Models"):
 * stand-in residual ``delta`` for the training objective: fp32 [M, V], N(0, 0.5).
 * block states for the residual-magnitude measurement: ``X^(0)`` ~ N(0, 2), then independent
   N(0, 0.4) increments per state (a random walk), fp32 [S, N] per block, optionally rounded to bf16.
+* transformer head body: every projection bf16 N(0, 0.02), norm gains 1.0; prefix key/value caches
+  bf16 [B, P_max, n_kv, head_dim], N(0, 1); prefix lengths uniform in [0, P_max] with sequence 0 at 0
+  and the last sequence at P_max.
 * verify logits: fp32 [B, L, V], N(0, 2); a +8 boost is *added by the caller*
   at the drafted (position, token) pairs selected by ``verify_boost_mask``.
 
@@ -39,7 +42,7 @@ import numpy as np
 SEED_BASE = 0x4D5250  # "MRP"
 
 # tensor ids (part of the seed)
-T_WLM, T_E, T_W1, T_W2, T_H, T_Z, T_SPIKE, T_VERIFY, T_BOOST, T_DELTA, T_STATES = range(11)
+T_WLM, T_E, T_W1, T_W2, T_H, T_Z, T_SPIKE, T_VERIFY, T_BOOST, T_DELTA, T_STATES, T_TF, T_KV, T_PLEN = range(14)
 
 WEIGHT_CHUNK_ROWS = 4096
 
@@ -245,6 +248,52 @@ def block_states(cfg_id: int, block: int, S: int, N: int, bf16: bool = False, ba
     out[1:] *= np.float32(step_std)
     np.cumsum(out, axis=0, out=out)
     return f32_to_bf16_bits(out) if bf16 else out
+
+
+@dataclass(frozen=True)
+class TBodyDims:
+    """Sizes of the transformer head body (the decoder layer of the backbone's family)."""
+
+    D: int
+    n_heads: int
+    n_kv_heads: int
+    head_dim: int
+    d_ff: int
+    P_max: int
+    rope_theta: float = 1.0e6
+
+
+def tf_layer(cfg: Config, td: TBodyDims, k: int, l: int, gain: str = "ones") -> dict:
+    """Layer ``l`` of head ``k``: bf16 bits of Wqkv [(nh+2nkv)hd, d], Wo [d, nh hd], Wgu [2 d_ff, d],
+    Wdown [d, d_ff], the two norm gains [d] and the prefix caches kc, vc [B, P_max, nkv, hd]."""
+    d, qd, kvd = cfg.d, td.n_heads * td.head_dim, td.n_kv_heads * td.head_dim
+    tag = (k * 64 + l) * 8
+    out = {
+        "Wqkv": _normal_bf16(cfg.cid, T_TF, qd + 2 * kvd, d, 0.02, extra=tag + 0),
+        "Wo": _normal_bf16(cfg.cid, T_TF, d, qd, 0.02, extra=tag + 1),
+        "Wgu": _normal_bf16(cfg.cid, T_TF, 2 * td.d_ff, d, 0.02, extra=tag + 2),
+        "Wdown": _normal_bf16(cfg.cid, T_TF, d, td.d_ff, 0.02, extra=tag + 3),
+    }
+    for n, name in enumerate(("g1", "g2")):
+        if gain == "ones":
+            out[name] = f32_to_bf16_bits(np.ones(d, dtype=np.float32))
+        else:
+            out[name] = f32_to_bf16_bits(1.0 + 0.1 * _rng(cfg.cid, T_TF, 1 << 20, tag + 4 + n)
+                                         .standard_normal(d, dtype=np.float32))
+    rows = cfg.B * td.P_max
+    cols = td.n_kv_heads * td.head_dim
+    shape = (cfg.B, td.P_max, td.n_kv_heads, td.head_dim)
+    out["kc"] = _normal_bf16(cfg.cid, T_KV, max(rows, 1), cols, 1.0, extra=tag + 0)[:rows].reshape(shape)
+    out["vc"] = _normal_bf16(cfg.cid, T_KV, max(rows, 1), cols, 1.0, extra=tag + 1)[:rows].reshape(shape)
+    return out
+
+
+def prefix_lens(cfg: Config, td: TBodyDims) -> np.ndarray:
+    """Committed prefix length per sequence: int32 [B] in [0, P_max]."""
+    p = _rng(cfg.cid, T_PLEN, 0).integers(0, td.P_max + 1, cfg.B).astype(np.int32)
+    p[0] = 0
+    p[-1] = td.P_max
+    return p
 
 
 def verify_logits(cfg: Config, seqs: Optional[Iterable[int]] = None) -> np.ndarray:

@@ -174,6 +174,92 @@ def residual_rms(X):
     return pair, delta
 
 
+class _TCfg(C.Structure):
+    _fields_ = [("D", C.c_int), ("n_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+                ("d_ff", C.c_int), ("P_max", C.c_int), ("rope_theta", C.c_double)]
+
+
+class _TBodyC(C.Structure):
+    _fields_ = [("t", C.POINTER(_TCfg))] + [(n, C.POINTER(C.c_void_p)) for n in
+                                             ("Wqkv", "Wo", "Wgu", "Wdown", "g1", "g2", "kc", "vc")] + \
+               [("prefix_len", C.c_void_p)]
+
+
+def make_tcfg(D, n_heads, n_kv_heads, head_dim, d_ff, P_max, rope_theta=1.0e6) -> _TCfg:
+    assert n_heads % n_kv_heads == 0 and head_dim % 2 == 0
+    return _TCfg(D, n_heads, n_kv_heads, head_dim, d_ff, P_max, rope_theta)
+
+
+LAYER_FIELDS = ("Wqkv", "Wo", "Wgu", "Wdown", "g1", "g2", "kc", "vc")
+
+
+def _check_layer(tc: _TCfg, d, B, layer):
+    """layer: dict with the eight arrays of LAYER_FIELDS (uint16 bf16 bits)."""
+    qd, kvd = tc.n_heads * tc.head_dim, tc.n_kv_heads * tc.head_dim
+    _chk(layer["Wqkv"], np.uint16, (qd + 2 * kvd, d)); _chk(layer["Wo"], np.uint16, (d, qd))
+    _chk(layer["Wgu"], np.uint16, (2 * tc.d_ff, d)); _chk(layer["Wdown"], np.uint16, (d, tc.d_ff))
+    _chk(layer["g1"], np.uint16, (d,)); _chk(layer["g2"], np.uint16, (d,))
+    _chk(layer["kc"], np.uint16, (B, tc.P_max, tc.n_kv_heads, tc.head_dim))
+    _chk(layer["vc"], np.uint16, (B, tc.P_max, tc.n_kv_heads, tc.head_dim))
+
+
+def _layer_arrays(tc, d, B, layers):
+    """layers: flat list of layer dicts -> dict of ctypes pointer arrays."""
+    n = max(len(layers), 1)
+    out = {}
+    for f in LAYER_FIELDS:
+        out[f] = (C.c_void_p * n)(*[l[f].ctypes.data for l in layers])
+    for l in layers:
+        _check_layer(tc, d, B, l)
+    return out
+
+
+def rope(x, pos, theta):
+    """Rotary embedding of one head vector (float64 [hd]) at position ``pos``; returns a new array."""
+    x = np.array(x, np.float64)
+    lib().orc_rope(_p(x), x.shape[0], C.c_double(pos), C.c_double(theta))
+    return x
+
+
+def tlayer(tc: _TCfg, layer, U, P, eps=1e-6, b=0):
+    """One transformer layer over the block rows U float64 [L][d] of sequence ``b`` with ``P`` prefix
+    positions; returns the new rows."""
+    L, d = U.shape
+    B = layer["kc"].shape[0]
+    _check_layer(tc, d, B, layer)
+    assert 0 <= P <= tc.P_max
+    U = np.array(U, np.float64)
+    off = b * tc.P_max * tc.n_kv_heads * tc.head_dim * 2
+    lib().orc_tlayer(C.byref(tc), d, L, C.c_double(eps), _p(layer["Wqkv"]), _p(layer["Wo"]), _p(layer["Wgu"]),
+                     _p(layer["Wdown"]), _p(layer["g1"]), _p(layer["g2"]),
+                     C.c_void_p(layer["kc"].ctypes.data + off), C.c_void_p(layer["vc"].ctypes.data + off), P, _p(U))
+    return U
+
+
+def head_transformer(cfg: _Cfg, tc: _TCfg, Wf, layers, prefix_len, gamma, E, cond_tok, hrun):
+    """Transformer head body on all rows.  Returns (u [M][d], y [M][d], hrun_after)."""
+    M, d = cfg.B * cfg.L, cfg.d
+    assert len(layers) == tc.D
+    _chk(Wf, np.uint16, (d, 2 * d)); _chk(gamma, np.uint16, (d,)); _chk(E, np.uint16)
+    prefix_len = _chk(np.ascontiguousarray(prefix_len, dtype=np.int32), np.int32, (cfg.B,))
+    assert prefix_len.min() >= 0 and prefix_len.max() <= tc.P_max
+    cond_tok = _chk(np.ascontiguousarray(cond_tok, dtype=np.int32), np.int32, (cfg.B,))
+    hrun = np.array(_chk(np.ascontiguousarray(hrun, dtype=np.float64), np.float64, (M, d)))
+    arr = _layer_arrays(tc, d, cfg.B, layers)
+    u = np.empty((M, d)); y = np.empty((M, d))
+    lib().orc_head_transformer(C.byref(cfg), C.byref(tc), _p(Wf), *[arr[f] for f in LAYER_FIELDS], _p(prefix_len),
+                               _p(gamma), _p(E), _p(cond_tok), _p(hrun), _p(u), _p(y))
+    return u, y, hrun
+
+
+@dataclass
+class TBody:
+    """Transformer bodies of the K heads of a chain: layers[k][l] is a layer dict."""
+    tcfg: _TCfg
+    layers: Sequence
+    prefix_len: np.ndarray
+
+
 @dataclass
 class ChainOut:
     z: np.ndarray            # [M][V] float64, final logit state
@@ -194,8 +280,9 @@ class ChainOut:
 
 
 def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, revealed_at=None,
-               cond_tok=None, protect_pos=None, dump_y=False, x_tok=None) -> ChainOut:
-    """One chain step.  ``z`` [M][V] and ``hrun`` [M][d] float64 are copied, not modified."""
+               cond_tok=None, protect_pos=None, dump_y=False, x_tok=None, tbody: Optional[TBody] = None) -> ChainOut:
+    """One chain step.  ``z`` [M][V] and ``hrun`` [M][d] float64 are copied, not modified.  With ``tbody``
+    every head is (fuse projection W1, transformer layers, gamma); its W2 entry is ignored."""
     M, d, V, K, B = cfg.B * cfg.L, cfg.d, cfg.V, cfg.K, cfg.B
     assert len(heads) == K
     _chk(E, np.uint16); _chk(W_lm, np.uint16, (V, d))
@@ -203,9 +290,12 @@ def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, reveal
     z = np.array(_chk(np.ascontiguousarray(z, dtype=np.float64), np.float64, (M, V)))
     hrun = np.array(_chk(np.ascontiguousarray(hrun, dtype=np.float64), np.float64, (M, d)))
     for (w1, w2, g) in heads:
-        _chk(w1, np.uint16, (d, 2 * d)); _chk(w2, np.uint16, (d, d)); _chk(g, np.uint16, (d,))
+        _chk(w1, np.uint16, (d, 2 * d)); _chk(g, np.uint16, (d,))
+        if tbody is None:
+            _chk(w2, np.uint16, (d, d))
     PT = C.c_void_p * max(K, 1)
-    w1s = PT(*[h[0].ctypes.data for h in heads]); w2s = PT(*[h[1].ctypes.data for h in heads])
+    w1s = PT(*[h[0].ctypes.data for h in heads])
+    w2s = PT(*[h[1].ctypes.data for h in heads]) if tbody is None else None
     gs = PT(*[h[2].ctypes.data for h in heads])
     tok = np.full((K + 1, M), -1, np.int32); conf = np.zeros((K + 1, M)); lse = np.zeros((K + 1, M))
     masked = np.ones(M, np.uint8) if masked is None else np.array(masked, np.uint8)
@@ -218,9 +308,22 @@ def chain_step(cfg: _Cfg, E, W_lm, heads: Sequence, z, hrun, masked=None, reveal
     y = np.empty((K, M, d)) if dump_y else None
     gap = np.full((K + 1, M), np.inf)
     x_tok = np.full(M, -1, np.int32) if x_tok is None else np.array(x_tok, np.int32)
-    lib().orc_chain_step(C.byref(cfg), _p(E), _p(W_lm), w1s, w2s, gs, _p(z), _p(hrun), _p(tok), _p(conf),
-                         _p(lse), _p(masked), _p(revealed_at), _p(cond_tok), _p(protect_pos), _p(dpos),
-                         _p(dtok), _p(rem), _p(y), _p(gap), _p(x_tok))
+    if tbody is None:
+        lib().orc_chain_step(C.byref(cfg), _p(E), _p(W_lm), w1s, w2s, gs, _p(z), _p(hrun), _p(tok), _p(conf),
+                             _p(lse), _p(masked), _p(revealed_at), _p(cond_tok), _p(protect_pos), _p(dpos),
+                             _p(dtok), _p(rem), _p(y), _p(gap), _p(x_tok))
+    else:
+        tc = tbody.tcfg
+        assert len(tbody.layers) == K and all(len(ls) == tc.D for ls in tbody.layers)
+        flat = [l for ls in tbody.layers for l in ls]
+        arr = _layer_arrays(tc, d, B, flat)
+        plen = _chk(np.ascontiguousarray(tbody.prefix_len, dtype=np.int32), np.int32, (B,))
+        assert plen.min() >= 0 and plen.max() <= tc.P_max
+        tb = _TBodyC(C.pointer(tc), *[C.cast(arr[f], C.POINTER(C.c_void_p)) for f in LAYER_FIELDS],
+                     C.c_void_p(plen.ctypes.data))
+        lib().orc_chain_step_tf(C.byref(cfg), _p(E), _p(W_lm), w1s, gs, _p(z), _p(hrun), _p(tok), _p(conf),
+                                _p(lse), _p(masked), _p(revealed_at), _p(cond_tok), _p(protect_pos), _p(dpos),
+                                _p(dtok), _p(rem), _p(y), _p(gap), _p(x_tok), C.byref(tb))
     return ChainOut(z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos, dpos, dtok, rem, y, gap,
                     x_tok)
 

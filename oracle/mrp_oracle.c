@@ -179,6 +179,157 @@ void orc_head_mlp(const orc_cfg *c, const uint16_t *W1, const uint16_t *W2, cons
     }
 }
 
+/* ---- transformer head body (Section 3.2: fuse projection, D transformer layers, shared LM head;
+ * D = 3 in Section 4.1) ----
+ * The paper fixes only that outline; the layer itself is the decoder layer of the backbone's
+ * model family, written out here:
+ *     n   = RMSNorm(u) g1
+ *     q_h = RoPE(Wq_h n, pos), k_g = RoPE(Wk_g n, pos), v_g = Wv_g n        pos = prefix_len[b] + i
+ *     o_h = softmax_t( q_h . k_t / sqrt(hd) ) v_t    over the prefix cache of kv head g = h / (nh / nkv)
+ *                                                    and the L rows of the block (no mask inside the block)
+ *     a   = u + Wo [o_0 .. o_{nh-1}]
+ *     m   = RMSNorm(a) g2
+ *     u'  = a + Wdown ( SiLU(Wgate m) * (Wup m) )
+ * Wqkv rows: nh query heads, then nkv key heads, then nkv value heads (hd rows each).  Wgu rows:
+ * d_ff gate rows, then d_ff up rows.  The prefix cache holds bf16 keys (already rotated) and values,
+ * [B][P_max][nkv][hd], of which sequence b uses the first prefix_len[b] positions. */
+typedef struct {
+    int D, n_heads, n_kv_heads, head_dim, d_ff, P_max;
+    double rope_theta;
+} orc_tcfg;
+
+/* rotate-half convention: entry j pairs with entry j + hd/2, angle pos * theta^(-2j/hd) */
+void orc_rope(double *x, int hd, double pos, double theta) {
+    const int half = hd / 2;
+    for (int j = 0; j < half; ++j) {
+        const double ang = pos * pow(theta, -2.0 * (double)j / (double)hd);
+        const double cs = cos(ang), sn = sin(ang);
+        const double a = x[j], b = x[j + half];
+        x[j] = a * cs - b * sn;
+        x[j + half] = b * cs + a * sn;
+    }
+}
+
+static void rmsnorm_gain(const double *x, const uint16_t *g, int d, double eps, double *out) {
+    double ss = 0.0;
+    for (int j = 0; j < d; ++j) ss += x[j] * x[j];
+    const double inv = 1.0 / sqrt(ss / d + eps);
+    for (int j = 0; j < d; ++j) out[j] = x[j] * inv * bf16_bits_to_double(g[j]);
+}
+
+static void matvec_bf16(const uint16_t *W, int rows, int cols, const double *x, double *out) {
+    for (int r = 0; r < rows; ++r) {
+        const uint16_t *w = W + (size_t)r * cols;
+        double acc = 0.0;
+        for (int k = 0; k < cols; ++k) acc += bf16_bits_to_double(w[k]) * x[k];
+        out[r] = acc;
+    }
+}
+
+/* One transformer layer over the L rows U [L][d] of sequence b (in place). */
+void orc_tlayer(const orc_tcfg *t, int d, int L, double eps, const uint16_t *Wqkv, const uint16_t *Wo,
+                const uint16_t *Wgu, const uint16_t *Wdown, const uint16_t *g1, const uint16_t *g2,
+                const uint16_t *kc_b, const uint16_t *vc_b, int P, double *U) {
+    const int nh = t->n_heads, nkv = t->n_kv_heads, hd = t->head_dim, ff = t->d_ff;
+    const int qd = nh * hd, kvd = nkv * hd, rep = nh / nkv, T = P + L;
+    double *n = (double *)malloc(sizeof(double) * d);
+    double *qkv = (double *)malloc(sizeof(double) * (size_t)L * (qd + 2 * kvd));
+    double *o = (double *)malloc(sizeof(double) * qd);
+    double *sc = (double *)malloc(sizeof(double) * T);
+    double *tmp = (double *)malloc(sizeof(double) * (d > 2 * ff ? d : 2 * ff));
+    double *act = (double *)malloc(sizeof(double) * ff);
+    double *A = (double *)malloc(sizeof(double) * (size_t)L * d);
+    for (int i = 0; i < L; ++i) {
+        double *r = qkv + (size_t)i * (qd + 2 * kvd);
+        rmsnorm_gain(U + (size_t)i * d, g1, d, eps, n);
+        matvec_bf16(Wqkv, qd + 2 * kvd, d, n, r);
+        for (int h = 0; h < nh; ++h) orc_rope(r + h * hd, hd, (double)(P + i), t->rope_theta);
+        for (int g = 0; g < nkv; ++g) orc_rope(r + qd + g * hd, hd, (double)(P + i), t->rope_theta);
+    }
+    for (int i = 0; i < L; ++i) {
+        const double *qi = qkv + (size_t)i * (qd + 2 * kvd);
+        for (int h = 0; h < nh; ++h) {
+            const int g = h / rep;
+            const double *q = qi + h * hd;
+            double mx = -INFINITY;
+            for (int tt = 0; tt < T; ++tt) {
+                double acc = 0.0;
+                if (tt < P) {
+                    const uint16_t *k = kc_b + ((size_t)tt * nkv + g) * hd;
+                    for (int e = 0; e < hd; ++e) acc += q[e] * bf16_bits_to_double(k[e]);
+                } else {
+                    const double *k = qkv + (size_t)(tt - P) * (qd + 2 * kvd) + qd + g * hd;
+                    for (int e = 0; e < hd; ++e) acc += q[e] * k[e];
+                }
+                sc[tt] = acc / sqrt((double)hd);
+                if (sc[tt] > mx) mx = sc[tt];
+            }
+            double den = 0.0;
+            for (int tt = 0; tt < T; ++tt) { sc[tt] = exp(sc[tt] - mx); den += sc[tt]; }
+            double *oh = o + h * hd;
+            for (int e = 0; e < hd; ++e) oh[e] = 0.0;
+            for (int tt = 0; tt < T; ++tt) {
+                const double pr = sc[tt] / den;
+                if (tt < P) {
+                    const uint16_t *v = vc_b + ((size_t)tt * nkv + g) * hd;
+                    for (int e = 0; e < hd; ++e) oh[e] += pr * bf16_bits_to_double(v[e]);
+                } else {
+                    const double *v = qkv + (size_t)(tt - P) * (qd + 2 * kvd) + qd + kvd + g * hd;
+                    for (int e = 0; e < hd; ++e) oh[e] += pr * v[e];
+                }
+            }
+        }
+        matvec_bf16(Wo, d, qd, o, tmp);
+        for (int j = 0; j < d; ++j) A[(size_t)i * d + j] = U[(size_t)i * d + j] + tmp[j];
+    }
+    for (int i = 0; i < L; ++i) {
+        double *a = A + (size_t)i * d;
+        rmsnorm_gain(a, g2, d, eps, n);
+        matvec_bf16(Wgu, 2 * ff, d, n, tmp);
+        for (int j = 0; j < ff; ++j) act[j] = tmp[j] / (1.0 + exp(-tmp[j])) * tmp[ff + j];
+        matvec_bf16(Wdown, d, ff, act, n);
+        for (int j = 0; j < d; ++j) U[(size_t)i * d + j] = a[j] + n[j];
+    }
+    free(n); free(qkv); free(o); free(sc); free(tmp); free(act); free(A);
+}
+
+/* Transformer head body for every sequence: u0 = Wf [hrun ; e], D layers, then as the MLP body:
+ * y = bf16(RMSNorm(u_D) gamma), hrun += u_D if carry_hidden.  The per-layer arrays have D entries. */
+void orc_head_transformer(const orc_cfg *c, const orc_tcfg *t, const uint16_t *Wf,
+                          const uint16_t *const *Wqkv, const uint16_t *const *Wo, const uint16_t *const *Wgu,
+                          const uint16_t *const *Wdown, const uint16_t *const *g1, const uint16_t *const *g2,
+                          const uint16_t *const *kc, const uint16_t *const *vc, const int32_t *prefix_len,
+                          const uint16_t *gamma, const uint16_t *E, const int32_t *cond_tok, double *hrun,
+                          double *u_out, double *y_out) {
+    const int d = c->d, L = c->L;
+    const size_t cache_b = (size_t)t->P_max * t->n_kv_heads * t->head_dim;
+#pragma omp parallel for schedule(dynamic)
+    for (int b = 0; b < c->B; ++b) {
+        double *x = (double *)malloc(sizeof(double) * 2 * d);
+        double *U = (double *)malloc(sizeof(double) * (size_t)L * d);
+        double *yn = (double *)malloc(sizeof(double) * d);
+        const uint16_t *e = E + (size_t)cond_tok[b] * d;
+        for (int i = 0; i < L; ++i) {
+            for (int j = 0; j < d; ++j) x[j] = hrun[((size_t)b * L + i) * d + j];
+            for (int j = 0; j < d; ++j) x[d + j] = bf16_bits_to_double(e[j]);
+            matvec_bf16(Wf, d, 2 * d, x, U + (size_t)i * d);
+        }
+        for (int l = 0; l < t->D; ++l)
+            orc_tlayer(t, d, L, c->rms_eps, Wqkv[l], Wo[l], Wgu[l], Wdown[l], g1[l], g2[l], kc[l] + b * cache_b,
+                       vc[l] + b * cache_b, prefix_len[b], U);
+        for (int i = 0; i < L; ++i) {
+            const size_t row = (size_t)b * L + i;
+            rmsnorm_gain(U + (size_t)i * d, gamma, d, c->rms_eps, yn);
+            for (int j = 0; j < d; ++j) {
+                if (y_out) y_out[row * d + j] = orc_bf16_round(yn[j]);
+                if (u_out) u_out[row * d + j] = U[(size_t)i * d + j];
+                if (c->carry_hidden) hrun[row * d + j] += U[(size_t)i * d + j];
+            }
+        }
+        free(x); free(U); free(yn);
+    }
+}
+
 /* z[i][v] += sum_c W_lm[v][c] * y[i][c]   (shared LM head, residual add) */
 void orc_lm_head_add(const uint16_t *W_lm, const double *y, double *z, int M, int V, int d) {
 #pragma omp parallel for collapse(2) schedule(static)
@@ -423,12 +574,22 @@ void orc_residual_rms(int n_blocks, int S, long N, const double *X, double *rms_
  *   gap     [(K+1)][M] top-2 logit gap per state (may be NULL)
  *   x_tok   [M] in/out: token recorded when a position is revealed (may be NULL unless
  *           remask_mode is 1) */
-void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
+/* Per-head transformer bodies for the chain: every array has K * D entries, head k's layer l at
+ * [k * D + l] (a module applied K times repeats its pointers). */
+typedef struct {
+    const orc_tcfg *t;
+    const uint16_t *const *Wqkv, *const *Wo, *const *Wgu, *const *Wdown, *const *g1, *const *g2, *const *kc,
+        *const *vc;
+    const int32_t *prefix_len;
+} orc_tbody;
+
+static void chain_impl(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
                     const uint16_t *const *W1, const uint16_t *const *W2,
                     const uint16_t *const *gamma, double *z, double *hrun, int32_t *tok,
                     double *conf, double *lse, uint8_t *masked, int8_t *revealed_at,
                     int32_t *cond_tok, int32_t *protect_pos, int32_t *draft_pos,
-                    int32_t *draft_tok, uint8_t *remasked, double *y_dump, double *gap, int32_t *x_tok) {
+                    int32_t *draft_tok, uint8_t *remasked, double *y_dump, double *gap, int32_t *x_tok,
+                    const orc_tbody *tb) {
     const int M = c->B * c->L, K = c->K, B = c->B;
     double *ptok = (c->remask_mode == 1) ? (double *)malloc(sizeof(double) * M) : NULL;
     int32_t *dp = (int32_t *)malloc(sizeof(int32_t) * B);
@@ -449,7 +610,14 @@ void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
     }
     for (int k = 1; k <= K; ++k) {
         const int state = c->state_offset + k;
-        orc_head_mlp(c, W1[k - 1], W2[k - 1], gamma[k - 1], E, cond_tok, hrun, NULL, y);
+        if (tb) {
+            const int o = (k - 1) * tb->t->D;
+            orc_head_transformer(c, tb->t, W1[k - 1], tb->Wqkv + o, tb->Wo + o, tb->Wgu + o, tb->Wdown + o,
+                                 tb->g1 + o, tb->g2 + o, tb->kc + o, tb->vc + o, tb->prefix_len, gamma[k - 1], E,
+                                 cond_tok, hrun, NULL, y);
+        } else {
+            orc_head_mlp(c, W1[k - 1], W2[k - 1], gamma[k - 1], E, cond_tok, hrun, NULL, y);
+        }
         if (y_dump) memcpy(y_dump + (size_t)(k - 1) * M * c->d, y, sizeof(double) * (size_t)M * c->d);
         orc_lm_head_add(W_lm, y, z, M, c->V, c->d);
         orc_reduce_rows(z, M, c->V, tok + (size_t)k * M, conf + (size_t)k * M, lse + (size_t)k * M,
@@ -473,4 +641,25 @@ void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
         }
     }
     free(dp); free(dt); free(y); free(ptok);
+}
+
+void orc_chain_step(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
+                    const uint16_t *const *W1, const uint16_t *const *W2,
+                    const uint16_t *const *gamma, double *z, double *hrun, int32_t *tok,
+                    double *conf, double *lse, uint8_t *masked, int8_t *revealed_at,
+                    int32_t *cond_tok, int32_t *protect_pos, int32_t *draft_pos,
+                    int32_t *draft_tok, uint8_t *remasked, double *y_dump, double *gap, int32_t *x_tok) {
+    chain_impl(c, E, W_lm, W1, W2, gamma, z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos,
+               draft_pos, draft_tok, remasked, y_dump, gap, x_tok, NULL);
+}
+
+/* The same chain with the transformer head body: W1[k] is head k's fuse projection, W2 is unused
+ * (may be NULL). */
+void orc_chain_step_tf(const orc_cfg *c, const uint16_t *E, const uint16_t *W_lm,
+                       const uint16_t *const *W1, const uint16_t *const *gamma, double *z, double *hrun,
+                       int32_t *tok, double *conf, double *lse, uint8_t *masked, int8_t *revealed_at,
+                       int32_t *cond_tok, int32_t *protect_pos, int32_t *draft_pos, int32_t *draft_tok,
+                       uint8_t *remasked, double *y_dump, double *gap, int32_t *x_tok, const orc_tbody *tb) {
+    chain_impl(c, E, W_lm, W1, NULL, gamma, z, hrun, tok, conf, lse, masked, revealed_at, cond_tok, protect_pos,
+               draft_pos, draft_tok, remasked, y_dump, gap, x_tok, tb);
 }

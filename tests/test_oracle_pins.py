@@ -681,3 +681,149 @@ def test_residual_rms_random_walk_statistics_and_bf16_range():
     tiny = np.zeros((1, 2, 8)); tiny[0, 0, :] = 1.0; tiny[0, 1, :] = 1.0 + 2.0 ** -7
     pair, delta = orc.residual_rms(tiny)
     np.testing.assert_allclose(delta[1], 2.0 ** -7, rtol=1e-15)
+
+
+# ---------------------------------------------------------------------------------------------
+# Transformer head body (Section 3.2; D = 3 in Section 4.1)
+def _tf_small(D=1, B=2, L=4, P_max=5, gain="normal"):
+    cfg = mi.config(0, d=32, V=64, B=B, L=L, K=1)
+    td = mi.TBodyDims(D, 4, 2, 8, 48, P_max, rope_theta=100.0)
+    tc = orc.make_tcfg(td.D, td.n_heads, td.n_kv_heads, td.head_dim, td.d_ff, td.P_max, td.rope_theta)
+    return cfg, td, tc, [mi.tf_layer(cfg, td, 0, l, gain=gain) for l in range(D)]
+
+
+def test_rope_closed_forms_and_relative_position():
+    """Rotary embedding: explicit 2-d and 4-d rotations, identity at position 0, norm kept, and
+    q.k after rotation depends only on the position difference."""
+    p, th = 3.0, 10000.0
+    np.testing.assert_allclose(orc.rope([1.0, 0.0], p, th), [np.cos(p), np.sin(p)], rtol=1e-15)
+    np.testing.assert_allclose(orc.rope([0.0, 1.0], p, th), [-np.sin(p), np.cos(p)], rtol=1e-15)
+    # hd = 4: entry 0 pairs with 2 at angle p, entry 1 pairs with 3 at angle p / sqrt(theta)
+    a2 = p / np.sqrt(th)
+    np.testing.assert_allclose(orc.rope([1.0, 2.0, 0.0, 0.0], p, th),
+                               [np.cos(p), 2 * np.cos(a2), np.sin(p), 2 * np.sin(a2)], rtol=1e-14)
+    q, k = RNG.normal(size=16), RNG.normal(size=16)
+    np.testing.assert_array_equal(orc.rope(q, 0.0, th), q)
+    np.testing.assert_allclose(np.linalg.norm(orc.rope(q, 77.0, th)), np.linalg.norm(q), rtol=1e-14)
+    d0 = orc.rope(q, 9.0, th) @ orc.rope(k, 4.0, th)
+    d1 = orc.rope(q, 109.0, th) @ orc.rope(k, 104.0, th)
+    np.testing.assert_allclose(d0, d1, rtol=1e-11)
+    assert abs(orc.rope(q, 9.0, th) @ orc.rope(k, 5.0, th) - d0) > 1e-3
+
+
+def _np_layer(td, layer, U, P, b, eps):
+    """The same layer with numpy/scipy library calls (matmul, softmax), vectorised over rows and heads."""
+    from scipy.special import softmax
+    f = mi.bf16_bits_to_f64
+    L, d = U.shape
+    nh, nkv, hd, ff = td.n_heads, td.n_kv_heads, td.head_dim, td.d_ff
+    rms = lambda x, g: x / np.sqrt((x ** 2).mean(-1, keepdims=True) + eps) * f(g)
+    qkv = rms(U, layer["g1"]) @ f(layer["Wqkv"]).T
+    q = qkv[:, :nh * hd].reshape(L, nh, hd)
+    k = qkv[:, nh * hd:(nh + nkv) * hd].reshape(L, nkv, hd)
+    v = qkv[:, (nh + nkv) * hd:].reshape(L, nkv, hd)
+    pos = P + np.arange(L)
+    inv = td.rope_theta ** (-np.arange(hd // 2) * 2.0 / hd)
+    ang = pos[:, None] * inv[None, :]
+    cs, sn = np.cos(ang)[:, None, :], np.sin(ang)[:, None, :]
+    rot = lambda x: np.concatenate([x[..., :hd // 2] * cs - x[..., hd // 2:] * sn,
+                                    x[..., hd // 2:] * cs + x[..., :hd // 2] * sn], -1)
+    q, k = rot(q), rot(k)
+    K_all = np.concatenate([f(layer["kc"][b, :P]), k], 0)          # [T][nkv][hd]
+    V_all = np.concatenate([f(layer["vc"][b, :P]), v], 0)
+    K_all = np.repeat(K_all, nh // nkv, axis=1); V_all = np.repeat(V_all, nh // nkv, axis=1)
+    sc = np.einsum("ihe,the->iht", q, K_all) / np.sqrt(hd)
+    o = np.einsum("iht,the->ihe", softmax(sc, axis=-1), V_all).reshape(L, nh * hd)
+    a = U + o @ f(layer["Wo"]).T
+    gu = rms(a, layer["g2"]) @ f(layer["Wgu"]).T
+    g, u = gu[:, :ff], gu[:, ff:]
+    return a + (g / (1 + np.exp(-g)) * u) @ f(layer["Wdown"]).T
+
+
+def test_transformer_layer_against_library_version():
+    cfg, td, tc, layers = _tf_small()
+    U = RNG.normal(0, 1, (cfg.L, cfg.d))
+    for b, P in ((0, 0), (1, 5), (1, 3)):
+        got = orc.tlayer(tc, layers[0], U, P, eps=1e-6, b=b)
+        want = _np_layer(td, layers[0], U, P, b, 1e-6)
+        np.testing.assert_allclose(got, want, rtol=1e-10, atol=1e-12)
+    # a different prefix or a different sequence's cache changes the result
+    assert np.abs(orc.tlayer(tc, layers[0], U, 5, b=1) - orc.tlayer(tc, layers[0], U, 4, b=1)).max() > 1e-4
+    assert np.abs(orc.tlayer(tc, layers[0], U, 5, b=1) - orc.tlayer(tc, layers[0], U, 5, b=0)).max() > 1e-4
+
+
+def test_transformer_layer_special_cases():
+    """Zero output projections make the layer the identity; zero keys make attention the plain mean
+    of the values; one row without a prefix attends to itself only; the order of prefix entries is
+    immaterial."""
+    cfg, td, tc, layers = _tf_small(gain="ones")
+    f = mi.bf16_bits_to_f64
+    lay = {k: v.copy() for k, v in layers[0].items()}
+    U = RNG.normal(0, 1, (cfg.L, cfg.d))
+    z = dict(lay); z["Wo"] = np.zeros_like(lay["Wo"]); z["Wdown"] = np.zeros_like(lay["Wdown"])
+    np.testing.assert_array_equal(orc.tlayer(tc, z, U, 5, b=1), U)
+    # uniform attention: key rows of Wqkv and the key cache are zero; the MLP is switched off
+    nh, nkv, hd = td.n_heads, td.n_kv_heads, td.head_dim
+    m = dict(lay); m["Wdown"] = np.zeros_like(lay["Wdown"])
+    m["Wqkv"] = lay["Wqkv"].copy(); m["Wqkv"][nh * hd:(nh + nkv) * hd] = 0
+    m["kc"] = np.zeros_like(lay["kc"])
+    P, b = 5, 1
+    got = orc.tlayer(tc, m, U, P, b=b)
+    n = U / np.sqrt((U ** 2).mean(-1, keepdims=True) + 1e-6)
+    v_blk = (n @ f(m["Wqkv"][(nh + nkv) * hd:]).T).reshape(cfg.L, nkv, hd)
+    v_mean = np.concatenate([f(m["vc"][b, :P]), v_blk], 0).mean(0)              # [nkv][hd]
+    o = np.repeat(v_mean, nh // nkv, axis=0).reshape(-1)                        # same for every row
+    np.testing.assert_allclose(got, U + (f(m["Wo"]) @ o)[None, :], rtol=1e-11, atol=1e-13)
+    # a single row, no prefix: softmax over one key is 1, so o = its own value whatever q, k are
+    s = dict(lay); s["Wdown"] = np.zeros_like(lay["Wdown"])
+    U1 = U[:1]
+    n1 = U1 / np.sqrt((U1 ** 2).mean(-1, keepdims=True) + 1e-6)
+    v1 = (n1 @ f(s["Wqkv"][(nh + nkv) * hd:]).T).reshape(nkv, hd)
+    o1 = np.repeat(v1, nh // nkv, axis=0).reshape(-1)
+    np.testing.assert_allclose(orc.tlayer(tc, s, U1, 0, b=0), U1 + (f(s["Wo"]) @ o1)[None, :], rtol=1e-11, atol=1e-13)
+    # permuting the prefix entries (keys and values together) changes nothing
+    perm = RNG.permutation(5)
+    pl = dict(lay); pl["kc"] = np.ascontiguousarray(lay["kc"][:, perm]); pl["vc"] = np.ascontiguousarray(lay["vc"][:, perm])
+    np.testing.assert_allclose(orc.tlayer(tc, pl, U, 5, b=1), orc.tlayer(tc, lay, U, 5, b=1), rtol=1e-12, atol=1e-14)
+
+
+def test_transformer_head_body_composition():
+    """Fuse projection -> D layers -> RMSNorm/bf16, per sequence with its own prefix length and
+    conditioning token; D = 0 is the bare fuse projection; the chain with this body equals the
+    head-by-head composition with the LM head and the row reduction."""
+    D = 2
+    cfg, td, tc, layers = _tf_small(D=D, B=3)
+    f = mi.bf16_bits_to_f64
+    E, W = mi.embedding(cfg), mi.lm_head(cfg)
+    w1, _, g = mi.head_weights(cfg, 0, gamma="normal")
+    g = mi.f32_to_bf16_bits((1.0 + 10 * mi.bf16_bits_to_f32(g)).astype(np.float32))
+    h = val(mi.hidden(cfg))
+    ctok = np.array([3, 17, 60], np.int32)
+    plen = np.array([0, 5, 2], np.int32)
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, tau=0.9)
+    u, y, h_after = orc.head_transformer(oc, tc, w1, layers, plen, g, E, ctok, h)
+    for b in range(cfg.B):
+        rows = slice(b * cfg.L, (b + 1) * cfg.L)
+        x = np.concatenate([h[rows], np.repeat(f(E[ctok[b]])[None], cfg.L, 0)], 1)
+        U = x @ f(w1).T
+        for l in range(D):
+            U = _np_layer(td, layers[l], U, int(plen[b]), b, 1e-6)
+        np.testing.assert_allclose(u[rows], U, rtol=1e-9, atol=1e-12)
+        yn = U / np.sqrt((U ** 2).mean(-1, keepdims=True) + 1e-6) * f(g)
+        yb = orc.bf16_round(yn)
+        assert np.mean(y[rows] == yb) > 0.999          # (a rounding tie may flip under 1e-9 noise)
+        np.testing.assert_allclose(y[rows], yb, rtol=2 ** -7)
+    np.testing.assert_allclose(h_after, h + u, rtol=1e-14)
+    tc0 = orc.make_tcfg(0, 4, 2, 8, 48, 5, 100.0)
+    u0, _, _ = orc.head_transformer(oc, tc0, w1, [], plen, g, E, ctok, h)
+    x = np.concatenate([h, np.repeat(f(E[ctok]), cfg.L, 0)], 1)
+    np.testing.assert_allclose(u0, x @ f(w1).T, rtol=1e-12, atol=1e-14)
+    # chain: state 0 picks cond_tok itself; compare with the composition around head_transformer
+    z0 = mi.logits0(cfg)
+    out = orc.chain_step(oc, E, W, [(w1, None, g)], z0, h, tbody=orc.TBody(tc, [layers], plen), dump_y=True)
+    tok0, conf0, lse0 = orc.reduce_rows(z0.astype(np.float64))
+    ct = np.zeros(cfg.B, np.int32)
+    orc.reveal(oc, 0, conf0, tok0, np.ones(cfg.M, np.uint8), np.full(cfg.M, -1, np.int8), ct)
+    u2, y2, _ = orc.head_transformer(oc, tc, w1, layers, plen, g, E, ct, h)
+    np.testing.assert_array_equal(out.y[0], y2)
+    np.testing.assert_allclose(out.z, z0 + y2 @ f(W).T, rtol=1e-12, atol=1e-12)
