@@ -214,6 +214,51 @@ int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const floa
                             uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
                             int32_t *correction_tok /* [B] */);
 
+/* Transformer head body (Section 3.2: the head "fuses [hidden states and token
+ * embeddings] via a learned projection, passes the result through a small
+ * number of transformer layers, and reuses the backbone's language model
+ * head"; D = 3 in Section 4.1).  The layer is the decoder layer of the
+ * backbone's model family:
+ *   u_0 = W1 [h_run ; E[cond_tok]]                        (the head's W1 is the fuse projection)
+ *   n = RMSNorm(u) g1;  q | k | v = Wqkv n;  rotary embedding (rotate-half,
+ *       base rope_theta) of q and k at position prefix_len[b] + i
+ *   o = softmax(q k^T / sqrt(head_dim)) v over the sequence's prefix cache
+ *       (positions 0 .. prefix_len[b]-1, keys already rotated) and the L rows
+ *       of the block itself, no mask inside the block, grouped-query heads
+ *   a = u + Wo o;  m = RMSNorm(a) g2;  u' = a + Wdown (SiLU(Wgate m) * (Wup m))
+ * after D layers: h_run += u_D, y = bf16(RMSNorm(u_D) gamma), delta = W_lm y
+ * as for the MLP body.  All weights bf16 packed with mrp_pack_weight:
+ *   Wqkv [(n_heads + 2 n_kv_heads) * 128][d]  rows: query heads, key heads, value heads
+ *   Wo   [d][n_heads * 128]      Wgu [2 d_ff][d]  rows: gate, then up      Wdown [d][d_ff]
+ *   g1, g2: bf16 [d], plain;  k_cache, v_cache: bf16 [B][max_prefix][n_kv_heads][128]
+ * (row b of a cache belongs to sequence b of the call; may be NULL when max_prefix = 0). */
+#define MRP_MAX_TLAYERS 16
+typedef struct {
+    int D;                 /* layers per head, 1..MRP_MAX_TLAYERS */
+    int n_heads, n_kv_heads, head_dim;   /* head_dim must be 128; (n_heads / n_kv_heads) * block_len <= 64 */
+    int d_ff;              /* multiple of 128 */
+    int max_prefix;        /* positions per sequence in every prefix cache */
+    float rope_theta;
+} mrp_tbody_dims;
+
+typedef struct {
+    const void *Wqkv_packed, *Wo_packed, *Wgu_packed, *Wdown_packed;
+    const void *g1, *g2;
+    const void *k_cache, *v_cache;
+} mrp_tlayer;
+
+/* Reserve the transformer body's workspace on the context's device (one
+ * hipMalloc, freed by mrp_destroy); once per context, block_len <= 16. */
+int mrp_tbody_create(mrp_ctx *ctx, const mrp_tbody_dims *dims);
+
+/* mrp_chain_step with the transformer head body: layers holds K * D entries,
+ * head k's layer l at [k * D + l] (one module applied K times repeats its
+ * entries); heads[k].W2_packed is ignored; prefix_len: device int32 [B],
+ * values clamped to [0, max_prefix].  Everything else as mrp_chain_step. */
+int mrp_chain_step_tf(mrp_ctx *ctx, void *stream, int B, int K, const void *h, float *h_run, const void *E,
+                      const void *W_lm_packed, const mrp_head *heads, const mrp_tlayer *layers,
+                      const int32_t *prefix_len, float *z, const mrp_reveal_cfg *cfg, const mrp_step_io *io);
+
 /* Training-side objective of the head (Section 3.3, Equation 3), forward and
  * gradient: for every row i with row_mask[i] != 0 (NULL = all rows),
  *   loss_rows[i] = scale * KL( softmax(teacher[i]) || softmax(student[i]) ),

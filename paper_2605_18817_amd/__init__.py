@@ -5,5 +5,5 @@ package only marshals arguments.  PyTorch is used for device memory and
 streams.  There is no CPU fallback: without the built library, or without a
 GPU, calls fail loudly.
 """
-from .binding import (MrpContext, RevealCfg, StepIO, Head, load_library, library_path,  # noqa: F401
+from .binding import (MrpContext, RevealCfg, StepIO, Head, TLayer, load_library, library_path,  # noqa: F401
                       MrpError, pack_weight, packed_bytes, EXPORTED_SYMBOLS)

@@ -10,7 +10,7 @@ from . import build as _build
 
 EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
-    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms",
+    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms", "mrp_tbody_create", "mrp_chain_step_tf",
     "mrp_profile_enable", "mrp_profile_read",
 ]
 
@@ -28,6 +28,16 @@ class _Dims(C.Structure):
 
 class _Head(C.Structure):
     _fields_ = [("W1_packed", C.c_void_p), ("W2_packed", C.c_void_p), ("gamma", C.c_void_p)]
+
+
+class _TBodyDims(C.Structure):
+    _fields_ = [("D", C.c_int), ("n_heads", C.c_int), ("n_kv_heads", C.c_int), ("head_dim", C.c_int),
+                ("d_ff", C.c_int), ("max_prefix", C.c_int), ("rope_theta", C.c_float)]
+
+
+class _TLayer(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("Wqkv_packed", "Wo_packed", "Wgu_packed", "Wdown_packed", "g1", "g2",
+                                          "k_cache", "v_cache")]
 
 
 class _RevealCfg(C.Structure):
@@ -78,6 +88,10 @@ def load_library():
                                 C.c_void_p, C.c_void_p]
     lib.mrp_residual_rms.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_long, C.c_void_p, C.c_int,
                                      C.c_void_p, C.c_void_p]
+    lib.mrp_tbody_create.argtypes = [C.c_void_p, C.POINTER(_TBodyDims)]
+    lib.mrp_chain_step_tf.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.POINTER(_Head), C.POINTER(_TLayer), C.c_void_p, C.c_void_p,
+                                      C.POINTER(_RevealCfg), C.POINTER(_StepIO)]
     lib.mrp_commit.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
                                C.c_void_p]
     lib.mrp_verify_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
@@ -125,6 +139,19 @@ class Head:
     W1_packed: object
     W2_packed: object
     gamma: object
+
+
+@dataclass
+class TLayer:
+    """One transformer layer of a head body (device tensors; weights packed with pack_weight)."""
+    Wqkv_packed: object
+    Wo_packed: object
+    Wgu_packed: object
+    Wdown_packed: object
+    g1: object
+    g2: object
+    k_cache: object
+    v_cache: object
 
 
 @dataclass
@@ -216,6 +243,30 @@ class MrpContext:
         rc = self.lib.mrp_chain_step(self._h, _stream(), B, K, _ptr(h), _ptr(h_run), _ptr(E), _ptr(W_lm_packed),
                                      harr, _ptr(z), C.byref(ccfg), C.byref(cio))
         return self._check(rc, "mrp_chain_step") if check else rc
+
+    def tbody_create(self, D: int, n_heads: int, n_kv_heads: int, d_ff: int, max_prefix: int,
+                     rope_theta: float = 1.0e6, head_dim: int = 128, check: bool = True) -> int:
+        dims = _TBodyDims(D, n_heads, n_kv_heads, head_dim, d_ff, max_prefix, rope_theta)
+        rc = self.lib.mrp_tbody_create(self._h, C.byref(dims))
+        return self._check(rc, "mrp_tbody_create") if check else rc
+
+    def chain_step_tf(self, B: int, K: int, h, h_run, E, W_lm_packed, heads: Sequence[Head],
+                      layers: Sequence[TLayer], prefix_len, z, cfg: RevealCfg, io: StepIO, check: bool = True) -> int:
+        """layers: K * D entries, head k's layer l at [k * D + l]."""
+        harr = (_Head * max(len(heads), 1))(*[_Head(_ptr(x.W1_packed), _ptr(x.W2_packed), _ptr(x.gamma))
+                                              for x in heads])
+        larr = (_TLayer * max(len(layers), 1))(*[
+            _TLayer(_ptr(l.Wqkv_packed), _ptr(l.Wo_packed), _ptr(l.Wgu_packed), _ptr(l.Wdown_packed), _ptr(l.g1),
+                    _ptr(l.g2), _ptr(l.k_cache), _ptr(l.v_cache)) for l in layers])
+        if len(heads) < K <= MRP_MAX_HEADS:
+            raise MrpError("fewer heads than K")
+        ccfg = _RevealCfg(cfg.tau, cfg.r_min, cfg.max_accept, cfg.carry_hidden, cfg.tau_remask, cfg.head_reveal,
+                          cfg.fresh_block, cfg.state_offset, cfg.run_state0, cfg.remask_mode)
+        cio = io.c_struct()
+        rc = self.lib.mrp_chain_step_tf(self._h, _stream(), B, K, _ptr(h), _ptr(h_run), _ptr(E), _ptr(W_lm_packed),
+                                        harr, larr if len(layers) else None, _ptr(prefix_len), _ptr(z),
+                                        C.byref(ccfg), C.byref(cio))
+        return self._check(rc, "mrp_chain_step_tf") if check else rc
 
     def remask(self, B: int, state: int, conf_new, tau_remask: float, protect_pos, revealed_at, masked,
                remasked_out, check: bool = True) -> int:

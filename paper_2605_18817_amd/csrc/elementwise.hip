@@ -25,27 +25,6 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__rest
     dst[ci] = v;
 }
 
-__device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
-
-// 8 fp32 values -> three 16-byte chunks (hi, mid, lo planes)
-__device__ __forceinline__ void split_chunk(const float (&x)[8], uint4 &hi, uint4 &mid, uint4 &lo) {
-    uint16_t h[8], m[8], l[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) split3(x[e], h[e], m[e], l[e]);
-    hi = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
-    mid = make_uint4(pack2(m[0], m[1]), pack2(m[2], m[3]), pack2(m[4], m[5]), pack2(m[6], m[7]));
-    lo = make_uint4(pack2(l[0], l[1]), pack2(l[2], l[3]), pack2(l[4], l[5]), pack2(l[6], l[7]));
-}
-
-__device__ __forceinline__ void unpack_bf16x8(const uint4 &u, float (&x)[8]) {
-    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        x[2 * e] = bf16_to_f32((uint16_t)(w[e] & 0xFFFFu));
-        x[2 * e + 1] = bf16_to_f32((uint16_t)(w[e] >> 16));
-    }
-}
-
 // from_h: hrun <- fp32(h), plane 0 <- h (exact).  else: planes <- split3(hrun).
 __global__ __launch_bounds__(256) void init_hidden_kernel(const uint16_t *__restrict__ h, float *__restrict__ hrun,
                                                           uint4 *__restrict__ xh, long plane_stride, int nIb, int M,
@@ -89,34 +68,6 @@ __global__ __launch_bounds__(256) void gather_e_kernel(const uint16_t *__restric
     }
 }
 
-// Sum over the k-split partial buffers of the 8 floats at `off` (same order for any batching:
-// ((p0 + p1) + p2) + ...).  Four splits are fetched at a time so their latencies overlap.
-__device__ __forceinline__ void sum_partials(const float *__restrict__ part, size_t split_stride, int nKs, size_t off,
-                                             float (&x)[8]) {
-#pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = 0.f;
-    int ks = 0;
-    for (; ks + 4 <= nKs; ks += 4) {
-        float4 a[4], b[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            const float4 *p = reinterpret_cast<const float4 *>(part + (size_t)(ks + u) * split_stride + off);
-            a[u] = p[0]; b[u] = p[1];
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            x[0] += a[u].x; x[1] += a[u].y; x[2] += a[u].z; x[3] += a[u].w;
-            x[4] += b[u].x; x[5] += b[u].y; x[6] += b[u].z; x[7] += b[u].w;
-        }
-    }
-    for (; ks < nKs; ++ks) {
-        const float4 *p = reinterpret_cast<const float4 *>(part + (size_t)ks * split_stride + off);
-        const float4 a = p[0], b = p[1];
-        x[0] += a.x; x[1] += a.y; x[2] += a.z; x[3] += a.w;
-        x[4] += b.x; x[5] += b.y; x[6] += b.z; x[7] += b.w;
-    }
-}
-
 __global__ __launch_bounds__(256) void silu_split_kernel(const float *__restrict__ part, int nKs,
                                                          uint4 *__restrict__ s_planes, long plane_stride, int nIb,
                                                          int M, int d) {
@@ -141,6 +92,7 @@ constexpr int NORM_MAX_CHUNKS = 4;  // per thread: d <= 8 * 256 * 4 = 8192
 // One workgroup per row: u = sum of k-split partials, RMSNorm -> bf16 y (packed),
 // h_run += u and the split planes of the new h_run for the next head.
 __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ part, int nKs,
+                                                   const float *__restrict__ resid,
                                                    const uint16_t *__restrict__ gamma, float eps,
                                                    float *__restrict__ hrun, bool carry, uint4 *__restrict__ y,
                                                    uint4 *__restrict__ xh, long plane_stride, int nIb, int M, int d) {
@@ -156,6 +108,12 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
         for (int e = 0; e < 8; ++e) u[n][e] = 0.f;
         if (c8 < C8) {
             sum_partials(part, (size_t)M * d, nKs, (size_t)i * d + 8 * c8, u[n]);
+            if (resid) {   // transformer body: u = residual stream + last projection
+                const float4 *rp = reinterpret_cast<const float4 *>(resid + (size_t)i * d + 8 * c8);
+                const float4 a = rp[0], b = rp[1];
+                u[n][0] += a.x; u[n][1] += a.y; u[n][2] += a.z; u[n][3] += a.w;
+                u[n][4] += b.x; u[n][5] += b.y; u[n][6] += b.z; u[n][7] += b.w;
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) ss += u[n][e] * u[n][e];
         }
@@ -226,9 +184,9 @@ hipError_t launch_silu_split(const float *part, int nKs, uint4 *s_planes, long p
     return hipGetLastError();
 }
 
-hipError_t launch_norm(const float *part, int nKs, const uint16_t *gamma, float eps, float *hrun, bool carry,
-                       uint4 *y, uint4 *xh, long plane_stride, int nIb, int M, int d, hipStream_t st) {
-    hipLaunchKernelGGL(norm_kernel, dim3(M), dim3(256), 0, st, part, nKs, gamma, eps, hrun, carry, y, xh,
+hipError_t launch_norm(const float *part, int nKs, const float *resid, const uint16_t *gamma, float eps, float *hrun,
+                       bool carry, uint4 *y, uint4 *xh, long plane_stride, int nIb, int M, int d, hipStream_t st) {
+    hipLaunchKernelGGL(norm_kernel, dim3(M), dim3(256), 0, st, part, nKs, resid, gamma, eps, hrun, carry, y, xh,
                        plane_stride, nIb, M, d);
     return hipGetLastError();
 }

@@ -33,6 +33,16 @@ struct mrp_ctx {
     float *kl_part, *kl_lse;   // KL loss: 5 partial arrays [max_rows * tiles], row log-sum-exps [2][max_rows]
     size_t kl_stride;
     double *rms_part;          // residual magnitudes: per-workgroup sums of squares
+    // transformer head body (mrp_tbody_create): its own allocation
+    bool tb_on;
+    mrp_tbody_dims tb;
+    char *tb_ws;
+    float *tb_U;               // residual stream [max_rows][d]
+    uint4 *tb_P;               // three activation planes, tb_plane uint4 each (widest of d, nh*hd, d_ff columns)
+    long tb_plane;
+    float *tb_part;            // partial sums, tb_part_floats floats
+    size_t tb_part_floats;
+    float2 *tb_rope;           // [max_rows][64]
     char err[512];
     bool prof_on;
     std::vector<hipEvent_t> ev;  // pairs
@@ -121,6 +131,36 @@ int pick_ksplit(int nVt, int nMg, int G, size_t part_rows, int M) {
     return want < 1 ? 1 : want;
 }
 
+// out[ks][M][R] = partial sums of W [R][Kc] (packed) times the activation planes; returns the number
+// of k splits written (1 for the tiled kernel) or -1 after a launch error (*err set).
+int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, const uint4 *act, long plane_stride,
+                 int nplanes, int M, float *out, size_t out_floats, hipError_t *err) {
+    if (c->use_tiled && M >= 768 && R % 256 == 0) {
+        TiledGemmArgs tg;
+        memset(&tg, 0, sizeof(tg));
+        tg.Wp = static_cast<const uint4 *>(Wp);
+        tg.KBw = Kc / 16; tg.n_rb = R / 32; tg.nIb = c->nIb; tg.M = M; tg.R = R;
+        tg.seg[0] = TiledSeg{act, plane_stride, Kc / 64, nplanes};
+        tg.nseg = 1;
+        tg.nMt = (M + 255) / 256; tg.nVt = R / 256;
+        tg.out = out;
+        *err = launch_tiled_gemm(tg, EPI_PARTIAL, st);
+        return *err == hipSuccess ? 1 : -1;
+    }
+    const int IT = stream_gemm_it(M);
+    StreamGemmArgs g;
+    memset(&g, 0, sizeof(g));
+    g.Wp = static_cast<const uint4 *>(Wp);
+    g.KBw = Kc / 16; g.n_rb = R / 32; g.nIb = c->nIb; g.M = M; g.R = R;
+    g.seg[0] = ActSeg{act, plane_stride, Kc / (16 * KSTEP), nplanes};
+    g.nseg = 1;
+    g.nVt = R / WG_ROWS; g.nMg = ((M + 31) / 32 + IT - 1) / IT; g.G = Kc / (16 * KSTEP);
+    g.nKs = pick_ksplit(g.nVt, g.nMg, g.G, out_floats / (size_t)R, M);
+    g.out = out;
+    *err = launch_stream_gemm(g, EPI_PARTIAL, st);
+    return *err == hipSuccess ? g.nKs : -1;
+}
+
 }  // namespace
 
 extern "C" {
@@ -141,6 +181,8 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     c->err[0] = 0;
     c->prof_on = false;
     c->ev_used = 0;
+    c->tb_on = false;
+    c->tb_ws = nullptr;
     {   // tuning switch: MRP_LM_PERSIST=0 routes M <= 128 through the generic stream GEMM
         const char *e = getenv("MRP_LM_PERSIST");
         c->lm_persist = !(e && e[0] == '0');
@@ -186,6 +228,7 @@ int mrp_destroy(mrp_ctx *c) {
     if (!c) return MRP_ERR_NULL;
     for (hipEvent_t e : c->ev) (void)hipEventDestroy(e);
     (void)hipFree(c->ws);
+    if (c->tb_ws) (void)hipFree(c->tb_ws);
     delete c;
     return MRP_OK;
 }
@@ -239,6 +282,46 @@ int mrp_residual_rms(mrp_ctx *c, void *stream, int n_blocks, int S, long N, cons
     return MRP_OK;
 }
 
+int mrp_tbody_create(mrp_ctx *c, const mrp_tbody_dims *t) {
+    if (!c || !t) return MRP_ERR_NULL;
+    if (c->tb_on) return fail(c, MRP_ERR_SHAPE, "mrp_tbody_create: already configured");
+    const int L = c->dims.block_len, d = c->dims.d;
+    if (t->D < 1 || t->D > MRP_MAX_TLAYERS || !tbody_shape_ok(t->n_heads, t->n_kv_heads, t->head_dim, L))
+        return fail(c, MRP_ERR_SHAPE,
+                    "mrp_tbody_create: need 1 <= D <= %d, head_dim 128, n_heads a multiple of n_kv_heads, block_len <= 16 "
+                    "and (n_heads / n_kv_heads) * block_len <= 64",
+                    MRP_MAX_TLAYERS);
+    if (t->d_ff < 128 || t->d_ff % 128 || t->d_ff > 65536 || t->max_prefix < 0 || !(t->rope_theta > 1.f))
+        return fail(c, MRP_ERR_SHAPE, "mrp_tbody_create: d_ff must be a multiple of 128, max_prefix >= 0, rope_theta > 1");
+    if (tbody_configure() != hipSuccess) return fail(c, MRP_ERR_HIP, "mrp_tbody_create: kernel attributes");
+    const int qd = t->n_heads * t->head_dim, qkvd = qd + 2 * t->n_kv_heads * t->head_dim;
+    int cmax = d > qd ? d : qd;
+    if (t->d_ff > cmax) cmax = t->d_ff;
+    int rmax = qkvd > 2 * t->d_ff ? qkvd : 2 * t->d_ff;
+    if (d > rmax) rmax = d;
+    c->tb_plane = (long)(cmax / 16) * c->nIb * 64;
+    c->tb_part_floats = c->part_rows * (size_t)rmax;
+    size_t o = 0;
+    auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
+    const size_t off_U = take((size_t)c->dims.max_rows * d * sizeof(float));
+    const size_t off_P = take((size_t)NSPLIT * c->tb_plane * 16);
+    const size_t off_part = take(c->tb_part_floats * sizeof(float));
+    const size_t off_rope = take((size_t)c->dims.max_rows * 64 * sizeof(float2));
+    if (hipMalloc(reinterpret_cast<void **>(&c->tb_ws), o) != hipSuccess || hipMemset(c->tb_ws, 0, o) != hipSuccess ||
+        hipDeviceSynchronize() != hipSuccess) {
+        if (c->tb_ws) (void)hipFree(c->tb_ws);
+        c->tb_ws = nullptr;
+        return fail(c, MRP_ERR_HIP, "mrp_tbody_create: allocating %zu bytes failed", o);
+    }
+    c->tb_U = reinterpret_cast<float *>(c->tb_ws + off_U);
+    c->tb_P = reinterpret_cast<uint4 *>(c->tb_ws + off_P);
+    c->tb_part = reinterpret_cast<float *>(c->tb_ws + off_part);
+    c->tb_rope = reinterpret_cast<float2 *>(c->tb_ws + off_rope);
+    c->tb = *t;
+    c->tb_on = true;
+    return MRP_OK;
+}
+
 int mrp_profile_enable(mrp_ctx *c, int on) {
     if (!c) return MRP_ERR_NULL;
     if (on && c->ev.empty()) {
@@ -262,9 +345,12 @@ int mrp_profile_read(mrp_ctx *c, float *ms_out, int cap) {
     return n;
 }
 
-int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float *h_run, const void *E,
-                   const void *W_lm_packed, const mrp_head *heads, float *z, const mrp_reveal_cfg *cfg,
-                   const mrp_step_io *io) {
+}  // extern "C"
+
+// layers == nullptr: MLP head body; else head k's transformer layers are layers[(k - 1) * D ..]
+static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, float *h_run, const void *E,
+                      const void *W_lm_packed, const mrp_head *heads, const mrp_tlayer *layers,
+                      const int32_t *prefix_len, float *z, const mrp_reveal_cfg *cfg, const mrp_step_io *io) {
     if (!c) return MRP_ERR_NULL;
     if (!h_run || !E || !W_lm_packed || !z || !cfg || !io || (K > 0 && !heads))
         return fail(c, MRP_ERR_NULL, "mrp_chain_step: required pointer is NULL");
@@ -281,10 +367,23 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
     const long Ml = (long)B * L;
     if (Ml > c->dims.max_rows) return fail(c, MRP_ERR_WORKSPACE, "rows %ld exceed max_rows %d", Ml, c->dims.max_rows);
     for (int k = 0; k < K; ++k) {
-        if (!heads[k].W1_packed || !heads[k].W2_packed || !heads[k].gamma)
+        if (!heads[k].W1_packed || (!layers && !heads[k].W2_packed) || !heads[k].gamma)
             return fail(c, MRP_ERR_NULL, "head %d has a NULL weight", k);
-        if (!aligned16(heads[k].W1_packed) || !aligned16(heads[k].W2_packed) || !aligned16(heads[k].gamma))
+        if (!aligned16(heads[k].W1_packed) || (!layers && !aligned16(heads[k].W2_packed)) || !aligned16(heads[k].gamma))
             return fail(c, MRP_ERR_ALIGN, "head %d weights must be 16-byte aligned", k);
+    }
+    if (layers) {
+        if (!c->tb_on) return fail(c, MRP_ERR_WORKSPACE, "transformer body: call mrp_tbody_create first");
+        if (!prefix_len) return fail(c, MRP_ERR_NULL, "transformer body: prefix_len is NULL");
+        for (int n = 0; n < K * c->tb.D; ++n) {
+            const mrp_tlayer &l = layers[n];
+            const void *ptrs[8] = {l.Wqkv_packed, l.Wo_packed, l.Wgu_packed, l.Wdown_packed, l.g1, l.g2, l.k_cache, l.v_cache};
+            for (int q = 0; q < 8; ++q) {
+                if (!ptrs[q] && !(q >= 6 && c->tb.max_prefix == 0))
+                    return fail(c, MRP_ERR_NULL, "transformer layer %d has a NULL pointer", n);
+                if (!aligned16(ptrs[q])) return fail(c, MRP_ERR_ALIGN, "transformer layer %d: pointers must be 16-byte aligned", n);
+            }
+        }
     }
     if ((h && !aligned16(h)) || !aligned16(h_run) || !aligned16(E) || !aligned16(W_lm_packed) || !aligned16(z))
         return fail(c, MRP_ERR_ALIGN, "tensor base pointers must be 16-byte aligned");
@@ -361,6 +460,44 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
             nks1 = g.nKs;
             HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
         }
+        const float *resid = nullptr;   // transformer body: residual stream added to the last projection
+        if (layers) {
+            const mrp_tbody_dims &tb = c->tb;
+            const int qd = tb.n_heads * tb.head_dim, qkvd = qd + 2 * tb.n_kv_heads * tb.head_dim, ff = tb.d_ff;
+            const size_t part_d = c->part_rows * (size_t)d;
+            hipError_t ge = hipSuccess;
+            if (k == 1)
+                HIP_TRY(c, launch_rope_table(prefix_len, B, L, tb.max_prefix, (double)tb.rope_theta, c->tb_rope, st));
+            // u_0 = fuse projection; planes <- RMSNorm(u_0) g1 of layer 0
+            int nks = nks1;
+            for (int l = 0; l < tb.D; ++l) {
+                const mrp_tlayer &ly = layers[(size_t)(k - 1) * tb.D + l];
+                HIP_TRY(c, launch_resid_norm_split(c->PART, nks, l == 0 ? nullptr : c->tb_U, c->tb_U,
+                                                   static_cast<const uint16_t *>(ly.g1), c->dims.rms_eps, c->tb_P,
+                                                   c->tb_plane, c->nIb, M, d, st));
+                nks = gemm_partial(c, st, ly.Wqkv_packed, qkvd, d, c->tb_P, c->tb_plane, NSPLIT, M, c->tb_part,
+                                   c->tb_part_floats, &ge);
+                HIP_TRY(c, ge);
+                HIP_TRY(c, launch_attention(c->tb_part, nks, M, B, L, tb.n_heads, tb.n_kv_heads, c->tb_rope,
+                                            static_cast<const uint16_t *>(ly.k_cache),
+                                            static_cast<const uint16_t *>(ly.v_cache), prefix_len, tb.max_prefix,
+                                            c->tb_P, c->tb_plane, c->nIb, st));
+                nks = gemm_partial(c, st, ly.Wo_packed, d, qd, c->tb_P, c->tb_plane, NSPLIT, M, c->PART, part_d, &ge);
+                HIP_TRY(c, ge);
+                // a = u + Wo o; planes <- RMSNorm(a) g2
+                HIP_TRY(c, launch_resid_norm_split(c->PART, nks, c->tb_U, c->tb_U, static_cast<const uint16_t *>(ly.g2),
+                                                   c->dims.rms_eps, c->tb_P, c->tb_plane, c->nIb, M, d, st));
+                nks = gemm_partial(c, st, ly.Wgu_packed, 2 * ff, d, c->tb_P, c->tb_plane, NSPLIT, M, c->tb_part,
+                                   c->tb_part_floats, &ge);
+                HIP_TRY(c, ge);
+                HIP_TRY(c, launch_swiglu_split(c->tb_part, nks, c->tb_P, c->tb_plane, c->nIb, M, ff, st));
+                nks = gemm_partial(c, st, ly.Wdown_packed, d, ff, c->tb_P, c->tb_plane, NSPLIT, M, c->PART, part_d, &ge);
+                HIP_TRY(c, ge);
+                // u' = a + (down projection): folded into the next layer's norm or into the final norm below
+            }
+            nks2 = nks;
+            resid = c->tb_U;
+        } else {
         HIP_TRY(c, launch_silu_split(c->PART, nks1, c->S, c->plane, c->nIb, M, d, st));
         // u = W2 s
         if (tiled) {
@@ -385,8 +522,9 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
             nks2 = g.nKs;
             HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
         }
+        }
         // h_run += u ; y = bf16(RMSNorm(u) * gamma)
-        HIP_TRY(c, launch_norm(c->PART, nks2, static_cast<const uint16_t *>(hd.gamma), c->dims.rms_eps, h_run,
+        HIP_TRY(c, launch_norm(c->PART, nks2, resid, static_cast<const uint16_t *>(hd.gamma), c->dims.rms_eps, h_run,
                                cfg->carry_hidden != 0, c->Y, c->XH, c->plane, c->nIb, M, d, st));
         if (cfg->carry_hidden) np_h = NSPLIT;
         // z += W_lm y, fused with the split-vocabulary (max, sum-exp, argmax) partials
@@ -445,6 +583,22 @@ int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float 
         HIP_TRY(c, launch_merge_select(sa, st));
     }
     return MRP_OK;
+}
+
+extern "C" {
+
+int mrp_chain_step(mrp_ctx *c, void *stream, int B, int K, const void *h, float *h_run, const void *E,
+                   const void *W_lm_packed, const mrp_head *heads, float *z, const mrp_reveal_cfg *cfg,
+                   const mrp_step_io *io) {
+    return chain_impl(c, stream, B, K, h, h_run, E, W_lm_packed, heads, nullptr, nullptr, z, cfg, io);
+}
+
+int mrp_chain_step_tf(mrp_ctx *c, void *stream, int B, int K, const void *h, float *h_run, const void *E,
+                      const void *W_lm_packed, const mrp_head *heads, const mrp_tlayer *layers,
+                      const int32_t *prefix_len, float *z, const mrp_reveal_cfg *cfg, const mrp_step_io *io) {
+    if (!c) return MRP_ERR_NULL;
+    if (K > 0 && !layers) return fail(c, MRP_ERR_NULL, "mrp_chain_step_tf: layers is NULL");
+    return chain_impl(c, stream, B, K, h, h_run, E, W_lm_packed, heads, K > 0 ? layers : nullptr, prefix_len, z, cfg, io);
 }
 
 int mrp_remask(mrp_ctx *c, void *stream, int B, int state, const float *conf_new, float tau_remask,

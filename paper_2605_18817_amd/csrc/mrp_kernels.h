@@ -121,6 +121,55 @@ __device__ __forceinline__ size_t act_chunk_index(int row, int c8, int nIb) {
     return ((size_t)kb * nIb + (row >> 5)) * 64 + (row & 31) + 32 * half;
 }
 
+__device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
+
+// 8 fp32 values -> three 16-byte chunks (hi, mid, lo planes)
+__device__ __forceinline__ void split_chunk(const float (&x)[8], uint4 &hi, uint4 &mid, uint4 &lo) {
+    uint16_t h[8], m[8], l[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) split3(x[e], h[e], m[e], l[e]);
+    hi = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
+    mid = make_uint4(pack2(m[0], m[1]), pack2(m[2], m[3]), pack2(m[4], m[5]), pack2(m[6], m[7]));
+    lo = make_uint4(pack2(l[0], l[1]), pack2(l[2], l[3]), pack2(l[4], l[5]), pack2(l[6], l[7]));
+}
+
+__device__ __forceinline__ void unpack_bf16x8(const uint4 &u, float (&x)[8]) {
+    const uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        x[2 * e] = bf16_to_f32((uint16_t)(w[e] & 0xFFFFu));
+        x[2 * e + 1] = bf16_to_f32((uint16_t)(w[e] >> 16));
+    }
+}
+
+// Sum over the k-split partial buffers of the 8 floats at `off` (same order for any batching:
+// ((p0 + p1) + p2) + ...).  Four splits are fetched at a time so their latencies overlap.
+__device__ __forceinline__ void sum_partials(const float *__restrict__ part, size_t split_stride, int nKs, size_t off,
+                                             float (&x)[8]) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 0.f;
+    int ks = 0;
+    for (; ks + 4 <= nKs; ks += 4) {
+        float4 a[4], b[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const float4 *p = reinterpret_cast<const float4 *>(part + (size_t)(ks + u) * split_stride + off);
+            a[u] = p[0]; b[u] = p[1];
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            x[0] += a[u].x; x[1] += a[u].y; x[2] += a[u].z; x[3] += a[u].w;
+            x[4] += b[u].x; x[5] += b[u].y; x[6] += b[u].z; x[7] += b[u].w;
+        }
+    }
+    for (; ks < nKs; ++ks) {
+        const float4 *p = reinterpret_cast<const float4 *>(part + (size_t)ks * split_stride + off);
+        const float4 a = p[0], b = p[1];
+        x[0] += a.x; x[1] += a.y; x[2] += a.z; x[3] += a.w;
+        x[4] += b.x; x[5] += b.y; x[6] += b.z; x[7] += b.w;
+    }
+}
+
 // ---- host-side launchers (defined in the .hip files) ----
 hipError_t launch_stream_gemm(const StreamGemmArgs &a, int epi, hipStream_t st);
 size_t stream_gemm_lds_bytes(int it);
@@ -139,8 +188,9 @@ hipError_t launch_gather_e(const uint16_t *E, const int32_t *cond_tok, uint4 *xe
                            int d, int V, hipStream_t st);
 hipError_t launch_silu_split(const float *part, int nKs, uint4 *s_planes, long plane_stride, int nIb,
                              int M, int d, hipStream_t st);
-hipError_t launch_norm(const float *part, int nKs, const uint16_t *gamma, float eps, float *hrun,
-                       bool carry, uint4 *y, uint4 *xh, long plane_stride, int nIb, int M, int d,
+// u = (resid ? resid : 0) + sum of partials; y = bf16(RMSNorm(u) gamma); carry: hrun += u and its planes
+hipError_t launch_norm(const float *part, int nKs, const float *resid, const uint16_t *gamma, float eps,
+                       float *hrun, bool carry, uint4 *y, uint4 *xh, long plane_stride, int nIb, int M, int d,
                        hipStream_t st);
 
 struct SelectArgs {
@@ -184,6 +234,20 @@ hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *ver
                          const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
                          int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
 int verify_chunks(int V);
+
+// transformer head body (tbody.hip)
+hipError_t tbody_configure();   // once per device
+bool tbody_shape_ok(int nh, int nkv, int head_dim, int L);
+hipError_t launch_rope_table(const int32_t *prefix_len, int B, int L, int P_max, double theta, float2 *out,
+                             hipStream_t st);
+hipError_t launch_resid_norm_split(const float *part, int nKs, const float *resid, float *stream,
+                                   const uint16_t *gain, float eps, uint4 *planes, long plane_stride, int nIb, int M,
+                                   int d, hipStream_t st);
+hipError_t launch_swiglu_split(const float *part, int nKs, uint4 *planes, long plane_stride, int nIb, int M, int ff,
+                               hipStream_t st);
+hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int nh, int nkv, const float2 *rope,
+                            const uint16_t *kc, const uint16_t *vc, const int32_t *prefix_len, int P_max,
+                            uint4 *o_planes, long plane_stride, int nIb, hipStream_t st);
 
 size_t residual_rms_part_bytes();
 int residual_rms_max_blocks();
