@@ -17,6 +17,8 @@ namespace {
 constexpr int HD = 128;   // head dimension (fixed)
 constexpr int TK = 128;   // prefix keys per tile
 constexpr int LB = 16;    // largest block length the attention kernel stages
+constexpr int KROW = HD + 8;   // padded key row in LDS (272 bytes)
+constexpr int SROW = TK + 4;   // padded score row: queries a wave works on side by side fall on different banks
 
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
@@ -118,7 +120,7 @@ __global__ __launch_bounds__(256) void swiglu_split_kernel(const float *__restri
 // (query qq = hrep * L + i: head g * rep + hrep, block row i) share the keys and values of head g.
 // Keys arrive in tiles (TK prefix positions from the bf16 cache, then the block's own L rows in
 // fp32); per tile: scores -> LDS, online softmax per query (running max / sum, rescale factor),
-// then the value sum, thread (dim e, query half) holding QH accumulators.
+// then the value sum.
 struct AttnArgs {
     const float *qkv;        // partial sums [nKs][M][ldq] of the q | k | v projection
     size_t split_stride;
@@ -132,53 +134,63 @@ struct AttnArgs {
     int nIb;
 };
 
+// sum over the k splits of one projection output, in split order; eight loads in flight at a time
 __device__ __forceinline__ float sum_col(const AttnArgs &a, size_t off) {
     float x = 0.f;
-    for (int ks = 0; ks < a.nKs; ++ks) x += a.qkv[(size_t)ks * a.split_stride + off];
+    for (int k0 = 0; k0 < a.nKs; k0 += 8) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (k0 + u < a.nKs) ? a.qkv[(size_t)(k0 + u) * a.split_stride + off] : 0.f;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x += v[u];
+    }
     return x;
 }
 
 // softmax bookkeeping of one tile: S[qq][0 .. ncols) holds raw scores (-inf = no key) and is
-// replaced by exp(score - new running max); four adjacent lanes share a query.
+// replaced by exp(score - new running max); 256 / NQ adjacent lanes share a query, lane `part`
+// taking columns part, part + TPQ, ...
 template <int NQ>
-__device__ __forceinline__ void softmax_tile(float (*S)[TK], float *run_m, float *run_l, float *rescale, int ncols) {
-    const int qq = threadIdx.x >> 2, part = threadIdx.x & 3;
-    if (qq < NQ) {
-        const int per = ncols >> 2, c0 = part * per;
-        float mx = -INFINITY;
-        for (int c = 0; c < per; ++c) mx = fmaxf(mx, S[qq][c0 + c]);
-        mx = fmaxf(mx, __shfl_xor(mx, 1));
-        mx = fmaxf(mx, __shfl_xor(mx, 2));
-        const float m_old = run_m[qq];
-        const float m_new = fmaxf(m_old, mx);   // finite: every tile holds at least one key
-        float sum = 0.f;
-        for (int c = 0; c < per; ++c) {
-            const float p = __expf(S[qq][c0 + c] - m_new);   // exp(-inf) = 0 for absent keys
-            S[qq][c0 + c] = p;
-            sum += p;
-        }
-        sum += __shfl_xor(sum, 1);
-        sum += __shfl_xor(sum, 2);
-        if (part == 0) {
-            const float f = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
-            rescale[qq] = f;
-            run_m[qq] = m_new;
-            run_l[qq] = run_l[qq] * f + sum;
-        }
+__device__ __forceinline__ void softmax_tile(float (*S)[SROW], float *run_m, float *run_l, float *rescale, int ncols) {
+    constexpr int TPQ = 256 / NQ;   // 4 .. 32 lanes per query, inside one wave
+    const int qq = threadIdx.x / TPQ, part = threadIdx.x % TPQ;
+    float mx = -INFINITY;
+    for (int c = part; c < ncols; c += TPQ) mx = fmaxf(mx, S[qq][c]);
+#pragma unroll
+    for (int off = TPQ / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
+    const float m_old = run_m[qq];
+    const float m_new = fmaxf(m_old, mx);   // finite: every tile holds at least one key
+    float sum = 0.f;
+    for (int c = part; c < ncols; c += TPQ) {
+        const float p = __expf(S[qq][c] - m_new);   // exp(-inf) = 0 for absent keys
+        S[qq][c] = p;
+        sum += p;
+    }
+#pragma unroll
+    for (int off = TPQ / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
+    if (part == 0) {
+        const float f = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
+        rescale[qq] = f;
+        run_m[qq] = m_new;
+        run_l[qq] = run_l[qq] * f + sum;
     }
 }
 
-template <int QH>
+template <int QP>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
-    constexpr int NQ = 2 * QH;   // query slots (Q <= NQ; unused slots hold zeros)
+    constexpr int NQ = 8 * QP;   // query slots (Q <= NQ; unused slots hold zeros)
     extern __shared__ float smem[];
     float (*qs)[HD] = reinterpret_cast<float (*)[HD]>(smem);                       // [NQ][HD] rotated, scaled
     float (*kb)[HD] = reinterpret_cast<float (*)[HD]>(smem + NQ * HD);             // [LB][HD] rotated block keys
     float (*vb)[HD] = reinterpret_cast<float (*)[HD]>(smem + (NQ + LB) * HD);      // [LB][HD] block values
-    float (*S)[TK] = reinterpret_cast<float (*)[TK]>(smem + (NQ + 2 * LB) * HD);   // [NQ][TK]
-    float *run_m = smem + (NQ + 2 * LB) * HD + NQ * TK;
+    float (*S)[SROW] = reinterpret_cast<float (*)[SROW]>(smem + (NQ + 2 * LB) * HD);   // [NQ][TK] (padded rows)
+    float *run_m = smem + (NQ + 2 * LB) * HD + NQ * SROW;
     float *run_l = run_m + NQ;
     float *rescale = run_l + NQ;
+    // the current prefix tile: keys with rows padded to KROW entries (a lane reading its own key row
+    // 16 bytes at a time then hits every LDS bank once per 16 lanes), values unpadded
+    uint16_t (*kt)[KROW] = reinterpret_cast<uint16_t (*)[KROW]>(rescale + NQ);
+    uint16_t (*vt)[HD] = reinterpret_cast<uint16_t (*)[HD]>(reinterpret_cast<uint16_t *>(rescale + NQ) + TK * KROW);
 
     const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int L = a.L, rep = a.nh / a.nkv, Q = rep * L;
@@ -186,6 +198,25 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     int P = a.prefix_len[b];
     P = P < 0 ? 0 : (P > a.P_max ? a.P_max : P);
     const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+
+    // ---- prefix tiles: a tile's keys and values are requested (16 bytes per lane, whole cache rows)
+    // while the previous tile is being worked on, then parked in LDS
+    uint4 kreg[TK * HD / 8 / 256], vreg[TK * HD / 8 / 256];
+    auto request = [&](int t0) {
+#pragma unroll
+        for (int n = 0; n < TK * HD / 8 / 256; ++n) {
+            const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
+            const int t = t0 + key;
+            kreg[n] = make_uint4(0, 0, 0, 0);
+            vreg[n] = make_uint4(0, 0, 0, 0);
+            if (t < P) {
+                const size_t off = (((size_t)b * a.P_max + t) * a.nkv + g) * HD + 8 * c;
+                kreg[n] = *reinterpret_cast<const uint4 *>(a.kc + off);
+                vreg[n] = *reinterpret_cast<const uint4 *>(a.vc + off);
+            }
+        }
+    };
+    if (P > 0) request(0);
 
     // ---- prologue: the block's q (rotated, scaled), k (rotated) and v for this kv head
     for (int idx = tid; idx < NQ * (HD / 2); idx += 256) {
@@ -217,54 +248,79 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     if (tid < NQ) { run_m[tid] = -INFINITY; run_l[tid] = 0.f; rescale[tid] = 0.f; }
     __syncthreads();
 
-    const int e_own = tid & (HD - 1), qh = tid >> 7;   // value phase: dimension and query half
-    float o[QH];
+    // register tiles: a thread works on 4 keys x QP queries (scores) and 4 dimensions x QP queries
+    // (values), so that one LDS read feeds four multiply-adds per query
+    const int lg = tid & 31, qg = tid >> 5;   // key group / dimension group, query group
+    float o[QP][4];
 #pragma unroll
-    for (int q = 0; q < QH; ++q) o[q] = 0.f;
+    for (int q = 0; q < QP; ++q)
+#pragma unroll
+        for (int dd = 0; dd < 4; ++dd) o[q][dd] = 0.f;
 
-    // ---- prefix tiles
     for (int t0 = 0; t0 < P; t0 += TK) {
-        {   // scores: thread = (key, query half)
-            const int key = tid & (TK - 1);
-            const int t = t0 + key;
-            float acc[QH];
 #pragma unroll
-            for (int q = 0; q < QH; ++q) acc[q] = 0.f;
-            if (t < P) {
-                const uint4 *kr = reinterpret_cast<const uint4 *>(a.kc + (((size_t)b * a.P_max + t) * a.nkv + g) * HD);
+        for (int n = 0; n < TK * HD / 8 / 256; ++n) {
+            const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
+            *reinterpret_cast<uint4 *>(&kt[key][8 * c]) = kreg[n];
+            *reinterpret_cast<uint4 *>(&vt[key][8 * c]) = vreg[n];
+        }
+        __syncthreads();
+        if (t0 + TK < P) request(t0 + TK);
+        {   // scores of keys lg, lg + 32, lg + 64, lg + 96 of the tile
+            float acc[QP][4];
+#pragma unroll
+            for (int q = 0; q < QP; ++q)
+#pragma unroll
+                for (int u = 0; u < 4; ++u) acc[q][u] = 0.f;
+            if (t0 + lg < P) {
 #pragma unroll 2
                 for (int c = 0; c < HD / 8; ++c) {
-                    float kf[8];
-                    unpack_bf16x8(kr[c], kf);
+                    float kf[4][8];
 #pragma unroll
-                    for (int q = 0; q < QH; ++q) {
-                        const float4 q0 = *reinterpret_cast<const float4 *>(&qs[qh * QH + q][8 * c]);
-                        const float4 q1 = *reinterpret_cast<const float4 *>(&qs[qh * QH + q][8 * c + 4]);
-                        acc[q] += q0.x * kf[0] + q0.y * kf[1] + q0.z * kf[2] + q0.w * kf[3] + q1.x * kf[4] +
-                                  q1.y * kf[5] + q1.z * kf[6] + q1.w * kf[7];
+                    for (int u = 0; u < 4; ++u)
+                        unpack_bf16x8(*reinterpret_cast<const uint4 *>(&kt[lg + 32 * u][8 * c]), kf[u]);
+#pragma unroll
+                    for (int q = 0; q < QP; ++q) {
+                        const float4 q0 = *reinterpret_cast<const float4 *>(&qs[qg * QP + q][8 * c]);
+                        const float4 q1 = *reinterpret_cast<const float4 *>(&qs[qg * QP + q][8 * c + 4]);
+#pragma unroll
+                        for (int u = 0; u < 4; ++u)
+                            acc[q][u] += q0.x * kf[u][0] + q0.y * kf[u][1] + q0.z * kf[u][2] + q0.w * kf[u][3] +
+                                         q1.x * kf[u][4] + q1.y * kf[u][5] + q1.z * kf[u][6] + q1.w * kf[u][7];
                     }
                 }
             }
 #pragma unroll
-            for (int q = 0; q < QH; ++q) S[qh * QH + q][key] = (t < P) ? acc[q] : -INFINITY;
+            for (int q = 0; q < QP; ++q)
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    S[qg * QP + q][lg + 32 * u] = (t0 + lg + 32 * u < P) ? acc[q][u] : -INFINITY;
         }
         __syncthreads();
         softmax_tile<NQ>(S, run_m, run_l, rescale, TK);
         __syncthreads();
-        {   // values: thread = (dimension, query half)
+        {   // values: dimensions 4 lg .. 4 lg + 3
 #pragma unroll
-            for (int q = 0; q < QH; ++q) o[q] *= rescale[qh * QH + q];
-            const int nk = (P - t0 < TK) ? (P - t0) : TK;
-            const uint16_t *vr = a.vc + (((size_t)b * a.P_max + t0) * a.nkv + g) * HD + e_own;
-            const size_t vstride = (size_t)a.nkv * HD;
+            for (int q = 0; q < QP; ++q) {
+                const float f = rescale[qg * QP + q];
+#pragma unroll
+                for (int dd = 0; dd < 4; ++dd) o[q][dd] *= f;
+            }
+            const int nk = (P - t0 < TK) ? (P - t0) : TK;   // (absent keys: probability 0, value 0)
             for (int k4 = 0; k4 < nk; k4 += 4) {
-                float v[4];
+                float v[4][4];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) v[u] = (k4 + u < nk) ? bf16_to_f32(vr[(size_t)(k4 + u) * vstride]) : 0.f;
+                for (int u = 0; u < 4; ++u) {
+                    const uint2 raw = *reinterpret_cast<const uint2 *>(&vt[k4 + u][4 * lg]);
+                    v[u][0] = __uint_as_float(raw.x << 16); v[u][1] = __uint_as_float(raw.x & 0xFFFF0000u);
+                    v[u][2] = __uint_as_float(raw.y << 16); v[u][3] = __uint_as_float(raw.y & 0xFFFF0000u);
+                }
 #pragma unroll
-                for (int q = 0; q < QH; ++q) {
-                    const float4 p = *reinterpret_cast<const float4 *>(&S[qh * QH + q][k4]);
-                    o[q] += p.x * v[0] + p.y * v[1] + p.z * v[2] + p.w * v[3];
+                for (int q = 0; q < QP; ++q) {
+                    const float4 p = *reinterpret_cast<const float4 *>(&S[qg * QP + q][k4]);
+#pragma unroll
+                    for (int dd = 0; dd < 4; ++dd)
+                        o[q][dd] += p.x * v[0][dd] + p.y * v[1][dd] + p.z * v[2][dd] + p.w * v[3][dd];
                 }
             }
         }
@@ -285,17 +341,28 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     softmax_tile<NQ>(S, run_m, run_l, rescale, 16);
     __syncthreads();
 #pragma unroll
-    for (int q = 0; q < QH; ++q) o[q] *= rescale[qh * QH + q];
-    for (int k = 0; k < L; ++k) {
-        const float v = vb[k][e_own];
+    for (int q = 0; q < QP; ++q) {
+        const float f = rescale[qg * QP + q];
 #pragma unroll
-        for (int q = 0; q < QH; ++q) o[q] += S[qh * QH + q][k] * v;
+        for (int dd = 0; dd < 4; ++dd) o[q][dd] *= f;
+    }
+    for (int k = 0; k < L; ++k) {
+        const float4 v = *reinterpret_cast<const float4 *>(&vb[k][4 * lg]);
+#pragma unroll
+        for (int q = 0; q < QP; ++q) {
+            const float pk = S[qg * QP + q][k];
+            o[q][0] += pk * v.x; o[q][1] += pk * v.y; o[q][2] += pk * v.z; o[q][3] += pk * v.w;
+        }
     }
     __syncthreads();
 
     // ---- normalise, stage as [query][dimension], write the three planes
 #pragma unroll
-    for (int q = 0; q < QH; ++q) S[qh * QH + q][e_own] = o[q] / run_l[qh * QH + q];   // (TK == HD)
+    for (int q = 0; q < QP; ++q) {
+        const float inv_l = 1.0f / run_l[qg * QP + q];
+        *reinterpret_cast<float4 *>(&S[qg * QP + q][4 * lg]) =
+            make_float4(o[q][0] * inv_l, o[q][1] * inv_l, o[q][2] * inv_l, o[q][3] * inv_l);   // (TK == HD)
+    }
     __syncthreads();
     for (int idx = tid; idx < Q * (HD / 8); idx += 256) {
         const int qq = idx / (HD / 8), c = idx % (HD / 8);
@@ -314,30 +381,31 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 
 static_assert(TK == HD, "the score tile doubles as the output staging buffer");
 
-template <int QH>
+template <int QP>
 constexpr size_t attn_lds_bytes() {
-    return sizeof(float) * ((size_t)(2 * QH + 2 * LB) * HD + (size_t)2 * QH * TK + 3 * 2 * QH);
+    return sizeof(float) * ((size_t)(8 * QP + 2 * LB) * HD + (size_t)8 * QP * SROW + 3 * 8 * QP) +
+           sizeof(uint16_t) * ((size_t)TK * KROW + (size_t)TK * HD);
 }
 
-template <int QH>
+template <int QP>
 hipError_t attn_configure_one() {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<QH>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes<QH>());
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<QP>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes<QP>());
 }
 
-template <int QH>
+template <int QP>
 hipError_t attn_launch_one(const AttnArgs &a, int B, hipStream_t st) {
-    hipLaunchKernelGGL(attn_kernel<QH>, dim3(a.nkv, B), dim3(256), attn_lds_bytes<QH>(), st, a);
+    hipLaunchKernelGGL(attn_kernel<QP>, dim3(a.nkv, B), dim3(256), attn_lds_bytes<QP>(), st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t tbody_configure() {
-    hipError_t e = attn_configure_one<4>();
+    hipError_t e = attn_configure_one<1>();
+    if (e == hipSuccess) e = attn_configure_one<2>();
+    if (e == hipSuccess) e = attn_configure_one<4>();
     if (e == hipSuccess) e = attn_configure_one<8>();
-    if (e == hipSuccess) e = attn_configure_one<16>();
-    if (e == hipSuccess) e = attn_configure_one<32>();
     return e;
 }
 
@@ -381,10 +449,10 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
     a.P_max = P_max; a.nh = nh; a.nkv = nkv; a.L = L;
     a.o_planes = o_planes; a.plane_stride = plane_stride; a.nIb = nIb;
     const int Q = (nh / nkv) * L;
-    if (Q <= 8) return attn_launch_one<4>(a, B, st);
-    if (Q <= 16) return attn_launch_one<8>(a, B, st);
-    if (Q <= 32) return attn_launch_one<16>(a, B, st);
-    return attn_launch_one<32>(a, B, st);
+    if (Q <= 8) return attn_launch_one<1>(a, B, st);
+    if (Q <= 16) return attn_launch_one<2>(a, B, st);
+    if (Q <= 32) return attn_launch_one<4>(a, B, st);
+    return attn_launch_one<8>(a, B, st);
 }
 
 }  // namespace mrp
