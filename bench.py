@@ -10,6 +10,10 @@ HBM-bound.  Inputs are seeded and synthetic and resident in HBM before the timed
 region.  Prints ONE JSON line.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--skip-cpu-baseline]
+
+Further workloads of the same library, each printing its own JSON line in the same format
+(--workload kl_loss | residual_rms | tbody): the training objective (forward + gradient), the
+residual-magnitude reducer, and the chain with the transformer head body.
 """
 from __future__ import annotations
 
@@ -40,8 +44,154 @@ def traffic_from_profile(cid: int):
         return None
 
 
+FP64_VECTOR_PEAK_TFLOPS = 78.6  # 256 CUs x 4 SIMDs x 16 lanes x 2 flop x 2.4 GHz
+
+
+def _time_steps(torch, step, warmup, steps):
+    """Wall time and HIP-event time (on the launch stream, which is torch's current stream) of `steps` calls."""
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for _ in range(steps):
+        step()
+    e1.record()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0, e0.elapsed_time(e1) * 1e-3
+
+
+def _line(metric, value, unit, args, elapsed, dtype, workload, roof, cpu):
+    return {"metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+            "ms_per_step": 1e3 * elapsed / args.steps, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": dtype, "data": "synthetic", "config": {"workload": workload},
+            "roofline": roof, "cpu_baseline": cpu}
+
+
+def bench_kl_loss(args, np, torch, mi, mrp) -> dict:
+    """Equation 3 forward + gradient on config-2-sized logits (1024 rows x 151936)."""
+    cfg = mi.CONFIGS[args.config if args.config != 1 else 2]
+    M, V = cfg.M, cfg.V
+    t = mi.logits0(cfg, step=1)
+    s = t + mi.residual(cfg)
+    mask = (np.arange(M) % 5 != 2).astype(np.uint8)
+    ctx = mrp.MrpContext(256, V, M, cfg.L)
+    t_d, s_d, m_d = torch.from_numpy(t).cuda(), torch.from_numpy(s).cuda(), torch.from_numpy(mask).cuda()
+    loss = torch.empty((M,), dtype=torch.float32, device="cuda")
+    grad = torch.empty((M, V), dtype=torch.float32, device="cuda")
+    elapsed, ev = _time_steps(torch, lambda: ctx.kl_loss(M, t_d, s_d, m_d, 1.0 / M, loss, grad), args.warmup, args.steps)
+    byt = 20.0 * M * V * (mask.mean())          # masked-out rows are neither read nor re-read (their gradient is written: +4MV)
+    byt += 4.0 * M * V * (1 - mask.mean())
+    ach = byt / (ev / args.steps) / 1e9
+    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": None, "kernel": "kl_partial_kernel + kl_finish_kernel + kl_grad_kernel",
+            "kernel_ms": 1e3 * ev / args.steps}
+    cpu = None
+    if not args.skip_cpu_baseline:
+        import oracle as orc
+        n = M
+        c0 = time.perf_counter()
+        orc.kl_loss(np.ascontiguousarray(t[:n]), np.ascontiguousarray(s[:n]), np.ascontiguousarray(mask[:n]), 1.0 / M)
+        c1 = time.perf_counter()
+        cpu = {"value": n / (c1 - c0), "unit": "rows/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n} of {M} rows, {c1 - c0:.1f} s wall, fp64, gcc -O2"}
+    ctx.close()
+    return _line("KL objective (Eq. 3) forward + gradient, rows/s on 1 GPU; % HBM roofline", M * args.steps / elapsed,
+                 "rows/s", args, elapsed, "f32", f"{M} rows x V={V} fp32 teacher and student logits, 80% of rows masked in",
+                 roof, cpu)
+
+
+def bench_residual_rms(args, np, torch, mi, mrp) -> dict:
+    """Appendix B magnitudes of 8 blocks of 17 logit states (16 x 151936 fp32 each)."""
+    nb, S, N = 8, 17, 16 * 151936
+    X = np.stack([mi.block_states(2, b, S, N) for b in range(nb)])
+    ctx = mrp.MrpContext(256, 4096, 16, 16)
+    X_d = torch.from_numpy(X).cuda()
+    pair = torch.empty((nb, S, S), dtype=torch.float64, device="cuda")
+    delta = torch.empty((S,), dtype=torch.float64, device="cuda")
+    elapsed, ev = _time_steps(torch, lambda: ctx.residual_rms(nb, S, N, X_d, False, pair, delta), args.warmup, args.steps)
+    flop = (136 + 2 * 153) * float(nb) * N       # per entry: 136 fp64 subtractions, 153 fused multiply-adds
+    ach = flop / (ev / args.steps) / 1e12
+    roof = {"bound": "alu", "achieved": ach, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": ach / FP64_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel": "rms_partial_kernel<17>",
+            "kernel_ms": 1e3 * ev / args.steps, "hbm_GBps": 4.0 * nb * S * N / (ev / args.steps) / 1e9}
+    cpu = None
+    if not args.skip_cpu_baseline:
+        import oracle as orc
+        n = N
+        Xs = np.ascontiguousarray(X[:1, :, :n].astype(np.float64))
+        c0 = time.perf_counter()
+        orc.residual_rms(Xs)
+        c1 = time.perf_counter()
+        cpu = {"value": (n / N) / (c1 - c0), "unit": "blocks/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n} of {N} entries of one block's 17 states, {c1 - c0:.1f} s wall, fp64, gcc -O2"}
+    ctx.close()
+    return _line("residual-magnitude blocks/s (App. B: 17 states of 16 x V logits) on 1 GPU; % fp64 vector roofline",
+                 nb * args.steps / elapsed, "blocks/s", args, elapsed, "f64",
+                 f"{nb} blocks x 17 states x {N} fp32 entries (random-walk stand-in states)", roof, cpu)
+
+
+def bench_tbody(args, np, torch, mi, mrp) -> dict:
+    """Config 1 with the transformer head body: D = 3 layers of the backbone family's shape at d = 2048
+    (16 query / 8 kv heads of 128, gated MLP 6144), prefix caches of 1024 positions, one module applied K times."""
+    cfg = mi.CONFIGS[1]
+    d, V, B, L, K, M = cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, cfg.M
+    td = mi.TBodyDims(D=3, n_heads=16, n_kv_heads=8, head_dim=128, d_ff=6144, P_max=1024)
+    bits = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    W, E = mi.lm_head(cfg), mi.embedding(cfg)
+    w1, _, g = mi.head_weights(cfg, 0)
+    layers_h = [mi.tf_layer(cfg, td, 0, l) for l in range(td.D)]
+    plen = mi.prefix_lens(cfg, td)
+    ctx = mrp.MrpContext(d, V, M, L)
+    ctx.tbody_create(td.D, td.n_heads, td.n_kv_heads, td.d_ff, td.P_max, td.rope_theta)
+    E_d, Wp_d = bits(E), mrp.pack_weight(bits(W))
+    head = mrp.Head(mrp.pack_weight(bits(w1)), None, bits(g))
+    layers = [mrp.TLayer(mrp.pack_weight(bits(l["Wqkv"])), mrp.pack_weight(bits(l["Wo"])), mrp.pack_weight(bits(l["Wgu"])),
+                         mrp.pack_weight(bits(l["Wdown"])), bits(l["g1"]), bits(l["g2"]), bits(l["kc"]), bits(l["vc"]))
+              for l in layers_h]
+    h_bits, z0 = mi.hidden(cfg), mi.logits0(cfg)
+    h_d, z_d, plen_d = bits(h_bits), torch.from_numpy(z0).cuda(), torch.from_numpy(plen).cuda()
+    hrun_d = torch.zeros((M, d), dtype=torch.float32, device="cuda")
+    io = mrp.StepIO(B, L, K)
+    rcfg = mrp.RevealCfg(tau=cfg.tau, fresh_block=1)
+    step = lambda: ctx.chain_step_tf(B, K, h_d, hrun_d, E_d, Wp_d, [head] * K, layers * K, plen_d, z_d, rcfg, io)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    elapsed, _ = _time_steps(torch, step, 0, args.steps)
+    lm_ms = ctx.profile_read()
+    lm_avg = float(np.mean(lm_ms))
+    ach = (2.0 * V * d + 8.0 * M * V) / (lm_avg * 1e-3) / 1e9
+    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": traffic_from_profile(1), "kernel": "lm_persist_kernel", "kernel_ms": lm_avg,
+            "lm_head_share_of_step": lm_avg * K / (1e3 * elapsed / args.steps)}
+    cpu = None
+    if not args.skip_cpu_baseline:
+        import oracle as orc
+        seqs = [0, B - 1]
+        rows = np.concatenate([np.arange(b * L, (b + 1) * L) for b in seqs])
+        oc = orc.make_cfg(d, V, len(seqs), L, K, tau=cfg.tau)
+        tc = orc.make_tcfg(td.D, td.n_heads, td.n_kv_heads, td.head_dim, td.d_ff, td.P_max, td.rope_theta)
+        sub = [dict(l, kc=np.ascontiguousarray(l["kc"][seqs]), vc=np.ascontiguousarray(l["vc"][seqs])) for l in layers_h]
+        c0 = time.perf_counter()
+        orc.chain_step(oc, E, W, [(w1, None, g)] * K, z0[rows].astype(np.float64), mi.bf16_bits_to_f64(h_bits[rows]),
+                       tbody=orc.TBody(tc, [sub] * K, plen[seqs]))
+        c1 = time.perf_counter()
+        cpu = {"value": len(rows) * K / (c1 - c0), "unit": "tokens/s", "cores": orc.threads(), "kind": "oracle",
+               "sample": f"sequences 0 and {B - 1} of {B} ({len(rows)} rows x {K} heads), {c1 - c0:.1f} s wall, fp64"}
+    ctx.close()
+    return _line("MRP draft tokens/sec per step with the transformer head body (D=3) on 1 GPU; % HBM roofline of the LM head",
+                 M * K * args.steps / elapsed, "tokens/s", args, elapsed, "bf16",
+                 f"config 1 sizes (d={d} V={V} B={B} block={L} K={K}), head body: 3 layers, 16/8 heads of 128, d_ff 6144, "
+                 f"prefix lengths uniform in [0, 1024]", roof, cpu)
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody"],
+                    help="chain (default): the headline metric; the others time further entry points")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
@@ -64,6 +214,11 @@ def main() -> int:
     if not torch.cuda.is_available():
         print("bench.py: no GPU; the MRP chain has no CPU path", file=sys.stderr)
         return 3
+
+    if args.workload != "chain":
+        fn = {"kl_loss": bench_kl_loss, "residual_rms": bench_residual_rms, "tbody": bench_tbody}[args.workload]
+        print(json.dumps(fn(args, np, torch, mi, mrp)))
+        return 0
 
     cfg = mi.CONFIGS[args.config]
     d, V, B, L, K, M = cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, cfg.M

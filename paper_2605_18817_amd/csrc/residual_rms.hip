@@ -162,27 +162,33 @@ template <typename F>
 __device__ __forceinline__ double wave_sum(int n, F &&get) {
     const int lane = threadIdx.x & 63;
     double v = 0.0;
-    for (int i = lane; i < n; i += 64) v += get(i);
+    int i = lane;
+    for (; i + 3 * 64 < n; i += 4 * 64) {   // four loads in flight, added in index order
+        const double a = get(i), b = get(i + 64), c = get(i + 128), d = get(i + 192);
+        v += a; v += b; v += c; v += d;
+    }
+    for (; i < n; i += 64) v += get(i);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off);
     return v;
 }
 
-// one workgroup per block, one wave per job in turn
+// one wave per (block, job): workgroup (x = block, y) holds jobs 4 y .. 4 y + 3
 __global__ __launch_bounds__(256) void rms_finish_kernel(const double *__restrict__ part, int S, long N, int nwg,
                                                          double *__restrict__ rms_pair) {
     const int blk = blockIdx.x, J = S * (S + 1) / 2, wave = threadIdx.x >> 6;
     double *out = rms_pair + (size_t)blk * S * S;
-    for (int i = threadIdx.x; i < S * S; i += 256)
-        if (i / S > i % S) out[i] = 0.0;   // below the diagonal
-    for (int r = 0; r < S; ++r)
-        for (int t = 0; t + r < S; ++t) {
-            const int p = job_index(S, r, t);
-            if ((p & 3) != wave) continue;
-            const double *src = part + ((size_t)blk * J + p) * nwg;
-            const double sum = wave_sum(nwg, [&](int w) { return src[w]; });
-            if ((threadIdx.x & 63) == 0) out[t * S + t + r] = sqrt(sum / (double)N);
-        }
+    if (blockIdx.y == 0)
+        for (int i = threadIdx.x; i < S * S; i += 256)
+            if (i / S > i % S) out[i] = 0.0;   // below the diagonal
+    const int p = 4 * blockIdx.y + wave;
+    if (p >= J) return;
+    int r = 0, first = 0;   // job p = (r, t): jobs of offset r start at first
+    while (p >= first + (S - r)) { first += S - r; ++r; }
+    const int t = p - first;
+    const double *src = part + ((size_t)blk * J + p) * nwg;
+    const double sum = wave_sum(nwg, [&](int w) { return src[w]; });
+    if ((threadIdx.x & 63) == 0) out[t * S + t + r] = sqrt(sum / (double)N);
 }
 
 // wave r: mean over blocks and offsets
@@ -235,7 +241,8 @@ hipError_t launch_residual_rms(int n_blocks, int S, long N, const void *X, bool 
         default: return hipErrorInvalidValue;
     }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(rms_finish_kernel, dim3(n_blocks), dim3(256), 0, st, part, S, N, (int)nwg, rms_pair);
+    hipLaunchKernelGGL(rms_finish_kernel, dim3(n_blocks, (S * (S + 1) / 2 + 3) / 4), dim3(256), 0, st, part, S, N,
+                       (int)nwg, rms_pair);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(rms_mean_kernel, dim3(S), dim3(64), 0, st, rms_pair, n_blocks, S, rms_delta);
