@@ -201,8 +201,8 @@ def main() -> int:
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (row or vocabulary sharding across GPUs is "
-              "described in DESIGN.md but not built); use --gpus 1", file=sys.stderr)
+        print("bench.py: this build runs on exactly one GPU (sequences would shard by rows, the vocabulary by "
+              "columns with one small all-gather per head; neither is built); use --gpus 1", file=sys.stderr)
         return 2
 
     import numpy as np
