@@ -35,7 +35,8 @@ constexpr int LM_NLD = LM_STAGE / LM_THREADS;  // u32x4 per thread per stage
 #ifndef MRP_LM_RING
 #define MRP_LM_RING 3
 #endif
-constexpr int LM_RING = MRP_LM_RING;           // k ranges of weight fragments held per wave (2..4)
+constexpr int LM_RING = MRP_LM_RING;           // k ranges of weight fragments held per wave (2 or 3)
+static_assert(LM_RING == 2 || LM_RING == 3, "ring depth");
 
 __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel(
     const LmPersistArgs a) {
@@ -193,7 +194,6 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     zload(0);
     LM_WLOAD(1)
     if constexpr (LM_RING >= 3) LM_WLOAD(2)
-    if constexpr (LM_RING >= 4) LM_WLOAD(3)
     __syncthreads();
 
     int g = 0, p = 0, buf = 0;  // k range, pass, LDS buffer
@@ -247,7 +247,6 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         iter(std::integral_constant<int, 0>{});
         iter(std::integral_constant<int, 1>{});
         if constexpr (LM_RING >= 3) iter(std::integral_constant<int, 2>{});
-        if constexpr (LM_RING >= 4) iter(std::integral_constant<int, 3>{});
     }
     if (tid < a.M) {
         const size_t o = (size_t)tid * a.nWG + wg;

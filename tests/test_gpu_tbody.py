@@ -100,6 +100,14 @@ def test_block_of_16_four_query_heads_per_kv_head():
     _run(cfg, td, mrp.RevealCfg(tau=0.9, tau_remask=0.5))
 
 
+@pytest.mark.parametrize("L,P_max", [(8, 260), (16, 400)])
+def test_two_kv_heads_prefix_over_several_tiles(L, P_max):
+    """16 and 32 query vectors per kv head (the two middle register-tile widths of the attention kernel)."""
+    cfg = mi.straddling(mi.config(0, d=512, B=2, L=L, K=1))
+    td = mi.TBodyDims(D=1, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=384, P_max=P_max)
+    _run(cfg, td, mrp.RevealCfg(tau=0.9))
+
+
 def test_no_prefix_three_layers_shared_module():
     cfg = mi.straddling(mi.config(0, B=2, L=4, K=3))
     td = mi.TBodyDims(D=3, n_heads=2, n_kv_heads=2, head_dim=128, d_ff=256, P_max=0)
