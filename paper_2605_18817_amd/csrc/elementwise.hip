@@ -29,10 +29,8 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__rest
 __global__ __launch_bounds__(256) void init_hidden_kernel(const uint16_t *__restrict__ h, float *__restrict__ hrun,
                                                           uint4 *__restrict__ xh, long plane_stride, int nIb, int M,
                                                           int d, bool from_h) {
-    const int C8 = d >> 3;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)M * C8) return;
-    const int i = (int)(idx / C8), c8 = (int)(idx % C8);
+    int i, c8;
+    if (!plane_block_lane((size_t)blockIdx.x * 4 + (threadIdx.x >> 6), d >> 4, M, i, c8)) return;
     const size_t dst = act_chunk_index(i, c8, nIb);
     if (from_h) {
         const uint4 v = *reinterpret_cast<const uint4 *>(h + (size_t)i * d + 8 * c8);
@@ -71,10 +69,8 @@ __global__ __launch_bounds__(256) void gather_e_kernel(const uint16_t *__restric
 __global__ __launch_bounds__(256) void silu_split_kernel(const float *__restrict__ part, int nKs,
                                                          uint4 *__restrict__ s_planes, long plane_stride, int nIb,
                                                          int M, int d) {
-    const int C8 = d >> 3;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)M * C8) return;
-    const int i = (int)(idx / C8), c8 = (int)(idx % C8);
+    int i, c8;
+    if (!plane_block_lane((size_t)blockIdx.x * 4 + (threadIdx.x >> 6), d >> 4, M, i, c8)) return;
     float x[8];
     sum_partials(part, (size_t)M * d, nKs, (size_t)i * d + 8 * c8, x);
 #pragma unroll
@@ -97,7 +93,8 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
                                                    float *__restrict__ hrun, bool carry, uint4 *__restrict__ y,
                                                    uint4 *__restrict__ xh, long plane_stride, int nIb, int M, int d) {
     __shared__ float wsum[4];
-    const int i = blockIdx.x;
+    const int i = xcd_row_of(blockIdx.x);
+    if (i >= M) return;   // (uniform over the workgroup)
     const int C8 = d >> 3;
     float u[NORM_MAX_CHUNKS][8];
     float ss = 0.f;
@@ -153,6 +150,10 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
 }
 
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
+// workgroups of 4 waves, one (k block, row block) unit per wave
+inline unsigned plane_blocks(int M, int cols) { return (unsigned)(((size_t)((M + 31) / 32) * (cols / 16) + 3) / 4); }
+// one workgroup per row, rows padded to whole XCD rounds of 32-row blocks
+inline unsigned xcd_row_blocks(int M) { return (unsigned)((M + 255) / 256 * 256); }
 
 }  // namespace
 
@@ -166,7 +167,7 @@ hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *ds
 
 hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb, int M,
                               int d, bool from_h, hipStream_t st) {
-    hipLaunchKernelGGL(init_hidden_kernel, dim3(blocks_for((size_t)M * (d / 8))), dim3(256), 0, st, h, hrun, xh,
+    hipLaunchKernelGGL(init_hidden_kernel, dim3(plane_blocks(M, d)), dim3(256), 0, st, h, hrun, xh,
                        plane_stride, nIb, M, d, from_h);
     return hipGetLastError();
 }
@@ -179,14 +180,14 @@ hipError_t launch_gather_e(const uint16_t *E, const int32_t *cond_tok, uint4 *xe
 
 hipError_t launch_silu_split(const float *part, int nKs, uint4 *s_planes, long plane_stride, int nIb, int M,
                              int d, hipStream_t st) {
-    hipLaunchKernelGGL(silu_split_kernel, dim3(blocks_for((size_t)M * (d / 8))), dim3(256), 0, st, part, nKs,
+    hipLaunchKernelGGL(silu_split_kernel, dim3(plane_blocks(M, d)), dim3(256), 0, st, part, nKs,
                        s_planes, plane_stride, nIb, M, d);
     return hipGetLastError();
 }
 
 hipError_t launch_norm(const float *part, int nKs, const float *resid, const uint16_t *gamma, float eps, float *hrun,
                        bool carry, uint4 *y, uint4 *xh, long plane_stride, int nIb, int M, int d, hipStream_t st) {
-    hipLaunchKernelGGL(norm_kernel, dim3(M), dim3(256), 0, st, part, nKs, resid, gamma, eps, hrun, carry, y, xh,
+    hipLaunchKernelGGL(norm_kernel, dim3(xcd_row_blocks(M)), dim3(256), 0, st, part, nKs, resid, gamma, eps, hrun, carry, y, xh,
                        plane_stride, nIb, M, d);
     return hipGetLastError();
 }

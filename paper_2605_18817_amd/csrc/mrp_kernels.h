@@ -121,6 +121,26 @@ __device__ __forceinline__ size_t act_chunk_index(int row, int c8, int nIb) {
     return ((size_t)kb * nIb + (row >> 5)) * 64 + (row & 31) + 32 * half;
 }
 
+// Elementwise producers of activation planes: wave `unit` owns the 1 KiB block (k block kb, row
+// block ib) of every plane, so that its 64 lanes store one contiguous block; the four waves of a
+// workgroup take four consecutive k blocks of the same row block (256 contiguous input bytes per row).
+// Returns false for a lane without a row.  c8: the lane's 8-column chunk.
+__device__ __forceinline__ bool plane_block_lane(size_t unit, int KB, int M, int &row, int &c8) {
+    const int lane = threadIdx.x & 63;
+    const int kb = (int)(unit % KB), ib = (int)(unit / KB);
+    row = ib * 32 + (lane & 31);
+    c8 = 2 * kb + (lane >> 5);
+    return row < M;
+}
+
+// Row handled by workgroup w of a one-row-per-workgroup kernel.  Consecutive workgroup ids go to
+// different XCDs (8, each with its own L2); this mapping gives every XCD whole 32-row blocks, so
+// the 16-byte pieces that 32 workgroups store into one 1 KiB plane block meet in one L2.
+__device__ __forceinline__ int xcd_row_of(int w) {
+    const int xcd = w & 7, slot = w >> 3;
+    return ((slot >> 5) * 8 + xcd) * 32 + (slot & 31);
+}
+
 __device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
 
 // 8 fp32 values -> three 16-byte chunks (hi, mid, lo planes)

@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256) void resid_norm_split_kernel(const float *__re
                                                                uint4 *__restrict__ planes, long plane_stride, int nIb,
                                                                int M, int d) {
     __shared__ float wsum[4];
-    const int i = blockIdx.x;
+    const int i = xcd_row_of(blockIdx.x);
+    if (i >= M) return;   // (uniform over the workgroup)
     const int C8 = d >> 3;
     float x[NORM_MAX_CHUNKS][8];
     float ss = 0.f;
@@ -98,10 +99,8 @@ __global__ __launch_bounds__(256) void resid_norm_split_kernel(const float *__re
 __global__ __launch_bounds__(256) void swiglu_split_kernel(const float *__restrict__ part, int nKs,
                                                            uint4 *__restrict__ planes, long plane_stride, int nIb,
                                                            int M, int ff) {
-    const int C8 = ff >> 3;
-    const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= (size_t)M * C8) return;
-    const int i = (int)(idx / C8), c8 = (int)(idx % C8);
+    int i, c8;
+    if (!plane_block_lane((size_t)blockIdx.x * 4 + (threadIdx.x >> 6), ff >> 4, M, i, c8)) return;
     float g[8], u[8], x[8];
     sum_partials(part, (size_t)M * 2 * ff, nKs, (size_t)i * 2 * ff + 8 * c8, g);
     sum_partials(part, (size_t)M * 2 * ff, nKs, (size_t)i * 2 * ff + ff + 8 * c8, u);
@@ -423,14 +422,14 @@ hipError_t launch_rope_table(const int32_t *prefix_len, int B, int L, int P_max,
 hipError_t launch_resid_norm_split(const float *part, int nKs, const float *resid, float *stream,
                                    const uint16_t *gain, float eps, uint4 *planes, long plane_stride, int nIb, int M,
                                    int d, hipStream_t st) {
-    hipLaunchKernelGGL(resid_norm_split_kernel, dim3(M), dim3(256), 0, st, part, nKs, resid, stream, gain, eps,
+    hipLaunchKernelGGL(resid_norm_split_kernel, dim3((M + 255) / 256 * 256), dim3(256), 0, st, part, nKs, resid, stream, gain, eps,
                        planes, plane_stride, nIb, M, d);
     return hipGetLastError();
 }
 
 hipError_t launch_swiglu_split(const float *part, int nKs, uint4 *planes, long plane_stride, int nIb, int M, int ff,
                                hipStream_t st) {
-    hipLaunchKernelGGL(swiglu_split_kernel, dim3(blocks_for((size_t)M * (ff / 8))), dim3(256), 0, st, part, nKs,
+    hipLaunchKernelGGL(swiglu_split_kernel, dim3((unsigned)(((size_t)((M + 31) / 32) * (ff / 16) + 3) / 4)), dim3(256), 0, st, part, nKs,
                        planes, plane_stride, nIb, M, ff);
     return hipGetLastError();
 }
