@@ -120,6 +120,48 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
         in_prot = a.write_protect ? -1 : a.protect_pos[b];
     }
 
+    if (a.row_stride == 1 && a.slot_stride > 1) {
+        // Layout [tile][row] (the GEMM kernels that own whole row tiles write it): the sequence's L
+        // rows of one tile are contiguous.  Thread (row p, group grp) merges tiles grp, grp + NG, ...
+        // in order, so a load instruction fetches whole 4 L-byte runs; the groups' results are then
+        // merged per row in group order.
+        __shared__ float g_m[256], g_s[256];
+        __shared__ int g_i[256];
+        int Lp = 1;
+        while (Lp < L) Lp <<= 1;
+        const int NG = 256 / Lp, p = threadIdx.x % Lp, grp = threadIdx.x / Lp;
+        Part pt = part_identity();
+        if (p < L) {
+            const size_t i = (size_t)b * L + p;
+            for (int t0 = grp; t0 < a.nT; t0 += NG * 8) {
+                float m[8], sx[8];
+                int ix[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {   // eight tiles in flight
+                    const int t = t0 + u * NG;
+                    const bool ok = t < a.nT;
+                    const size_t o = (size_t)(ok ? t : 0) * a.slot_stride + i;
+                    m[u] = ok ? a.pm[o] : -INFINITY;
+                    sx[u] = ok ? a.ps[o] : 0.f;
+                    ix[u] = ok ? a.pi[o] : 0x7fffffff;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) pt = part_merge(pt, Part{m[u], sx[u], ix[u]});
+            }
+        }
+        g_m[threadIdx.x] = pt.m; g_s[threadIdx.x] = pt.s; g_i[threadIdx.x] = pt.i;
+        __syncthreads();
+        if (threadIdx.x < L) {
+            const int q = threadIdx.x;
+            Part r = part_identity();
+            for (int gq = 0; gq < NG; ++gq) r = part_merge(r, Part{g_m[gq * Lp + q], g_s[gq * Lp + q], g_i[gq * Lp + q]});
+            const int i = b * L + q;
+            const float conf = 1.0f / r.s;
+            const float lse = r.m + logf(r.s);
+            a.tok[i] = r.i; a.conf[i] = conf; a.lse[i] = lse;
+            s_lse[q] = lse; s_conf[q] = conf; s_tok[q] = r.i;
+        }
+    } else {
     // one wavefront per row: merge the row's nT partials in a fixed order
     for (int p = wave; p < L; p += 4) {
         const int i = b * L + p;
@@ -150,6 +192,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
             s_conf[p] = conf;
             s_tok[p] = pt.i;
         }
+    }
     }
     __syncthreads();
 
