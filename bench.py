@@ -146,9 +146,10 @@ def bench_tbody(args, np, torch, mi, mrp) -> dict:
     ctx = mrp.MrpContext(d, V, M, L)
     ctx.tbody_create(td.D, td.n_heads, td.n_kv_heads, td.d_ff, td.P_max, td.rope_theta)
     E_d, Wp_d = bits(E), mrp.pack_weight(bits(W))
-    head = mrp.Head(mrp.pack_weight(bits(w1)), None, bits(g))
-    layers = [mrp.TLayer(mrp.pack_weight(bits(l["Wqkv"])), mrp.pack_weight(bits(l["Wo"])), mrp.pack_weight(bits(l["Wgu"])),
-                         mrp.pack_weight(bits(l["Wdown"])), bits(l["g1"]), bits(l["g2"]), bits(l["kc"]), bits(l["vc"]))
+    head = mrp.Head(mrp.pack_weight(bits(w1), body=True), None, bits(g))
+    pk = lambda a: mrp.pack_weight(bits(a), body=True)
+    layers = [mrp.TLayer(pk(l["Wqkv"]), pk(l["Wo"]), pk(l["Wgu"]),
+                         pk(l["Wdown"]), bits(l["g1"]), bits(l["g2"]), bits(l["kc"]), bits(l["vc"]))
               for l in layers_h]
     h_bits, z0 = mi.hidden(cfg), mi.logits0(cfg)
     h_d, z_d, plen_d = bits(h_bits), torch.from_numpy(z0).cuda(), torch.from_numpy(plen).cuda()
@@ -235,7 +236,7 @@ def main() -> int:
     w_d = dev_bits(W)
     Wp_d = mrp.pack_weight(w_d)
     del w_d
-    heads_d = [mrp.Head(mrp.pack_weight(dev_bits(w1)), mrp.pack_weight(dev_bits(w2)), dev_bits(g))
+    heads_d = [mrp.Head(mrp.pack_weight(dev_bits(w1), body=True), mrp.pack_weight(dev_bits(w2), body=True), dev_bits(g))
                for (w1, w2, g) in heads_h]
     h_bits = mi.hidden(cfg)
     h_d = dev_bits(h_bits)

@@ -18,8 +18,9 @@
  *   - Arguments are validated on the host before anything is launched; a
  *     failed validation returns a negative status and launches nothing.
  *   - Rows: M = B * L, row i belongs to sequence b = i / L, position p = i % L.
- *   - bf16 tensors are raw 16-bit patterns.  "packed" bf16 matrices are in the
- *     MFMA fragment order produced by mrp_pack_weight (see below).
+ *   - bf16 tensors are raw 16-bit patterns.  "packed" matrices are in the
+ *     MFMA fragment order produced by mrp_pack_weight (the LM head) or
+ *     mrp_pack_body_weight (every weight of a head body), see below.
  *   - Ties: an argmax over the vocabulary takes the lowest index; "most
  *     confident" ties take the lowest position.
  */
@@ -58,7 +59,7 @@ typedef struct {
 } mrp_dims;
 
 /* One head's weights (device).  W1: [d][2d], W2: [d][d], both packed with
- * mrp_pack_weight; gamma: bf16 [d], plain.  Head body (benchmark layout
+ * mrp_pack_body_weight; gamma: bf16 [d], plain.  Head body (benchmark layout
  * standing in for the transformer layers of Section 3.2):
  *   x = [h_run ; E[cond_tok]],  a = W1 x,  s = a * sigmoid(a),  u = W2 s,
  *   h_run += u (hidden residual, Algorithm 2 line "h <- h + Delta"),
@@ -157,6 +158,16 @@ const char *mrp_last_error(const mrp_ctx *ctx);
 size_t mrp_packed_bytes(int rows, int cols);
 int mrp_pack_weight(void *stream, const void *src /* bf16 [rows][cols] */, int rows, int cols,
                     void *dst /* mrp_packed_bytes(rows, cols), 16-B aligned */);
+/* The same layout with every value converted from bf16 to fp16 (round to
+ * nearest even): the form the head bodies take their weights in (W1, W2 and
+ * the transformer layers' projections).  The head body multiplies fp32
+ * activations, split into two fp16 terms, by these weights on the fp16 matrix
+ * cores with fp32 accumulation; the shared LM head keeps bf16 operands (its
+ * activation is bf16 by definition, Section 3.2).  The conversion is exact for
+ * 6.1e-5 <= |w| < 65504 and within 3e-8 for smaller magnitudes; activations of
+ * the head body must stay below 65504 in magnitude. */
+int mrp_pack_body_weight(void *stream, const void *src /* bf16 [rows][cols] */, int rows, int cols,
+                         void *dst /* mrp_packed_bytes(rows, cols), 16-B aligned */);
 
 /* One denoising step's chain (Algorithm 2 inner loop / Algorithm 3 drafting
  * loop / Algorithm 4 with tau_remask): state 0 = reduce z and reveal, then for
@@ -227,7 +238,7 @@ int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const floa
  *       of the block itself, no mask inside the block, grouped-query heads
  *   a = u + Wo o;  m = RMSNorm(a) g2;  u' = a + Wdown (SiLU(Wgate m) * (Wup m))
  * after D layers: h_run += u_D, y = bf16(RMSNorm(u_D) gamma), delta = W_lm y
- * as for the MLP body.  All weights bf16 packed with mrp_pack_weight:
+ * as for the MLP body.  All weights given as bf16 and packed with mrp_pack_body_weight:
  *   Wqkv [(n_heads + 2 n_kv_heads) * 128][d]  rows: query heads, key heads, value heads
  *   Wo   [d][n_heads * 128]      Wgu [2 d_ff][d]  rows: gate, then up      Wdown [d][d_ff]
  *   g1, g2: bf16 [d], plain;  k_cache, v_cache: bf16 [B][max_prefix][n_kv_heads][128]

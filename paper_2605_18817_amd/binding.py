@@ -10,7 +10,7 @@ from . import build as _build
 
 EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
-    "mrp_pack_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms", "mrp_tbody_create", "mrp_chain_step_tf",
+    "mrp_pack_weight", "mrp_pack_body_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms", "mrp_tbody_create", "mrp_chain_step_tf",
     "mrp_profile_enable", "mrp_profile_read",
 ]
 
@@ -77,6 +77,7 @@ def load_library():
     lib.mrp_packed_bytes.argtypes = [C.c_int, C.c_int]
     lib.mrp_packed_bytes.restype = C.c_size_t
     lib.mrp_pack_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+    lib.mrp_pack_body_weight.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
     lib.mrp_chain_step.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                    C.c_void_p, C.POINTER(_Head), C.c_void_p, C.POINTER(_RevealCfg),
                                    C.POINTER(_StepIO)]
@@ -120,15 +121,17 @@ def packed_bytes(rows: int, cols: int) -> int:
     return load_library().mrp_packed_bytes(rows, cols)
 
 
-def pack_weight(w):
-    """bf16 (or int16 bit pattern) device tensor [rows][cols] -> packed device tensor (uint8)."""
+def pack_weight(w, body: bool = False):
+    """bf16 (or int16 bit pattern) device tensor [rows][cols] -> packed device tensor (uint8).
+    body=True: a head-body weight (converted to fp16 while packing); False: the LM head."""
     import torch
     rows, cols = w.shape
     n = packed_bytes(rows, cols)
     if n == 0:
         raise MrpError(f"cannot pack a {rows}x{cols} matrix (cols must be a multiple of 16)")
     out = torch.empty(n, dtype=torch.uint8, device=w.device)
-    rc = load_library().mrp_pack_weight(_stream(), _ptr(w), rows, cols, _ptr(out))
+    fn = load_library().mrp_pack_body_weight if body else load_library().mrp_pack_weight
+    rc = fn(_stream(), _ptr(w), rows, cols, _ptr(out))
     if rc != 0:
         raise MrpError(f"mrp_pack_weight failed: {rc}")
     return out
@@ -143,7 +146,7 @@ class Head:
 
 @dataclass
 class TLayer:
-    """One transformer layer of a head body (device tensors; weights packed with pack_weight)."""
+    """One transformer layer of a head body (device tensors; weights packed with pack_weight(body=True))."""
     Wqkv_packed: object
     Wo_packed: object
     Wgu_packed: object

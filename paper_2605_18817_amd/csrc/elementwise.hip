@@ -10,7 +10,7 @@ namespace mrp {
 namespace {
 
 __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__restrict__ src, int rows, int cols,
-                                                          uint4 *__restrict__ dst, size_t nchunks) {
+                                                          uint4 *__restrict__ dst, size_t nchunks, bool to_f16) {
     const size_t ci = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (ci >= nchunks) return;
     const int KB = cols >> 4;
@@ -22,10 +22,10 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(const uint16_t *__rest
     const int col = kb * 16 + 8 * (lane >> 5);
     uint4 v = make_uint4(0, 0, 0, 0);
     if (row < rows) v = *reinterpret_cast<const uint4 *>(src + (size_t)row * cols + col);
-    dst[ci] = v;
+    dst[ci] = to_f16 ? bf16x8_to_f16x8(v) : v;
 }
 
-// from_h: hrun <- fp32(h), plane 0 <- h (exact).  else: planes <- split3(hrun).
+// from_h: hrun <- fp32(h), plane 0 <- fp16(h).  else: planes <- split2(hrun).
 __global__ __launch_bounds__(256) void init_hidden_kernel(const uint16_t *__restrict__ h, float *__restrict__ hrun,
                                                           uint4 *__restrict__ xh, long plane_stride, int nIb, int M,
                                                           int d, bool from_h) {
@@ -39,16 +39,12 @@ __global__ __launch_bounds__(256) void init_hidden_kernel(const uint16_t *__rest
         float4 *hp = reinterpret_cast<float4 *>(hrun + (size_t)i * d + 8 * c8);
         hp[0] = make_float4(x[0], x[1], x[2], x[3]);
         hp[1] = make_float4(x[4], x[5], x[6], x[7]);
-        xh[dst] = v;
+        xh[dst] = bf16x8_to_f16x8(v);
     } else {
         const float4 *hp = reinterpret_cast<const float4 *>(hrun + (size_t)i * d + 8 * c8);
         const float4 a = hp[0], b = hp[1];
         const float x[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
-        uint4 hi, mid, lo;
-        split_chunk(x, hi, mid, lo);
-        xh[dst] = hi;
-        xh[dst + plane_stride] = mid;
-        xh[dst + 2 * plane_stride] = lo;
+        split_store(x, xh, dst, plane_stride);
     }
 }
 
@@ -61,7 +57,7 @@ __global__ __launch_bounds__(256) void gather_e_kernel(const uint16_t *__restric
     tokc = tokc < 0 ? 0 : (tokc >= V ? V - 1 : tokc);
     const uint4 *erow = reinterpret_cast<const uint4 *>(E + (size_t)tokc * d);
     for (int c8 = threadIdx.x; c8 < C8; c8 += 256) {
-        const uint4 v = erow[c8];
+        const uint4 v = bf16x8_to_f16x8(erow[c8]);
         for (int p = 0; p < L; ++p) xe[act_chunk_index(b * L + p, c8, nIb)] = v;
     }
 }
@@ -75,12 +71,7 @@ __global__ __launch_bounds__(256) void silu_split_kernel(const float *__restrict
     sum_partials(part, (size_t)M * d, nKs, (size_t)i * d + 8 * c8, x);
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = x[e] / (1.0f + expf(-x[e]));  // SiLU
-    uint4 hi, mid, lo;
-    split_chunk(x, hi, mid, lo);
-    const size_t dst = act_chunk_index(i, c8, nIb);
-    s_planes[dst] = hi;
-    s_planes[dst + plane_stride] = mid;
-    s_planes[dst + 2 * plane_stride] = lo;
+    split_store(x, s_planes, act_chunk_index(i, c8, nIb), plane_stride);
 }
 
 constexpr int NORM_MAX_CHUNKS = 4;  // per thread: d <= 8 * 256 * 4 = 8192
@@ -139,11 +130,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
                                     b.x + u[n][4], b.y + u[n][5], b.z + u[n][6], b.w + u[n][7]};
                 hp[0] = make_float4(x[0], x[1], x[2], x[3]);
                 hp[1] = make_float4(x[4], x[5], x[6], x[7]);
-                uint4 hi, mid, lo;
-                split_chunk(x, hi, mid, lo);
-                xh[dst] = hi;
-                xh[dst + plane_stride] = mid;
-                xh[dst + 2 * plane_stride] = lo;
+                split_store(x, xh, dst, plane_stride);
             }
         }
     }
@@ -157,11 +144,11 @@ inline unsigned xcd_row_blocks(int M) { return (unsigned)((M + 255) / 256 * 256)
 
 }  // namespace
 
-hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, hipStream_t st) {
+hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, bool to_f16, hipStream_t st) {
     const size_t rpad = ((size_t)rows + 31) / 32 * 32;
     const size_t nchunks = rpad * cols / 8;
     hipLaunchKernelGGL(pack_weight_kernel, dim3(blocks_for(nchunks)), dim3(256), 0, st, src, rows, cols, dst,
-                       nchunks);
+                       nchunks, to_f16);
     return hipGetLastError();
 }
 

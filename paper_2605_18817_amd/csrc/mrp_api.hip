@@ -240,13 +240,21 @@ size_t mrp_packed_bytes(int rows, int cols) {
     return ((size_t)rows + 31) / 32 * 32 * (size_t)cols * 2;
 }
 
-int mrp_pack_weight(void *stream, const void *src, int rows, int cols, void *dst) {
+static int pack_impl(void *stream, const void *src, int rows, int cols, void *dst, bool to_f16) {
     if (!src || !dst) return MRP_ERR_NULL;
     if (rows < 1 || cols < 16 || cols % 16) return MRP_ERR_SHAPE;
     if (!aligned16(src) || !aligned16(dst)) return MRP_ERR_ALIGN;
-    hipError_t e = launch_pack_weight(static_cast<const uint16_t *>(src), rows, cols, static_cast<uint4 *>(dst),
+    hipError_t e = launch_pack_weight(static_cast<const uint16_t *>(src), rows, cols, static_cast<uint4 *>(dst), to_f16,
                                       static_cast<hipStream_t>(stream));
     return e == hipSuccess ? MRP_OK : MRP_ERR_HIP;
+}
+
+int mrp_pack_weight(void *stream, const void *src, int rows, int cols, void *dst) {
+    return pack_impl(stream, src, rows, cols, dst, false);
+}
+
+int mrp_pack_body_weight(void *stream, const void *src, int rows, int cols, void *dst) {
+    return pack_impl(stream, src, rows, cols, dst, true);
 }
 
 int mrp_kl_loss(mrp_ctx *c, void *stream, int M, const float *teacher, const float *student, const uint8_t *row_mask,

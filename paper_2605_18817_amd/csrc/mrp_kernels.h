@@ -7,12 +7,18 @@
 namespace mrp {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-// Number of bf16 terms an fp32 activation is split into before it enters a
-// bf16 MFMA (hi + mid + lo reproduces the fp32 value to ~2^-25), so that the
-// head body is computed to fp32 accuracy although the matrix cores take bf16.
-constexpr int NSPLIT = 3;
+// Number of fp16 terms an fp32 activation is split into before it enters an
+// fp16 MFMA: hi + lo reproduces the fp32 value to 2^-22 relative (or 2^-25
+// absolute where lo is subnormal; the matrix cores honour fp16 subnormals), so
+// the head body is computed to fp32 accuracy although the matrix cores take
+// 16-bit operands.  The head body's weights are converted from bf16 to fp16
+// when they are packed (exact for 6.1e-5 <= |w| < 65504, within 3e-8 below);
+// activations must stay below 65504 in magnitude.  The LM head itself runs on
+// bf16 operands (its activation y is bf16 by definition).
+constexpr int NSPLIT = 2;
 
 constexpr int MAX_L = 64;         // largest block length (rows per sequence)
 constexpr int KSTEP = 8;          // 16-wide k blocks per pipeline stage (128 k)
@@ -105,13 +111,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float x) {
 }
 __device__ __forceinline__ float bf16_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
 
-// hi/mid/lo bf16 terms of an fp32 value (each remainder is exact in fp32)
-__device__ __forceinline__ void split3(float x, uint16_t &hi, uint16_t &mid, uint16_t &lo) {
-    hi = f32_to_bf16_rne(x);
-    const float r1 = x - bf16_to_f32(hi);
-    mid = f32_to_bf16_rne(r1);
-    const float r2 = r1 - bf16_to_f32(mid);
-    lo = f32_to_bf16_rne(r2);
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float x) {
+    const _Float16 h = (_Float16)x;   // round to nearest even
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ float f16_bits_to_f32(uint16_t b) { return (float)__builtin_bit_cast(_Float16, b); }
+
+// hi/lo fp16 terms of an fp32 value (the remainder is exact in fp32)
+__device__ __forceinline__ void split2(float x, uint16_t &hi, uint16_t &lo) {
+    hi = f32_to_f16_bits(x);
+    lo = f32_to_f16_bits(x - f16_bits_to_f32(hi));
 }
 
 // index (in uint4 units) of the 16-byte chunk holding X[row][8*c8 .. 8*c8+7]
@@ -143,14 +152,13 @@ __device__ __forceinline__ int xcd_row_of(int w) {
 
 __device__ __forceinline__ uint32_t pack2(uint16_t lo, uint16_t hi) { return (uint32_t)lo | ((uint32_t)hi << 16); }
 
-// 8 fp32 values -> three 16-byte chunks (hi, mid, lo planes)
-__device__ __forceinline__ void split_chunk(const float (&x)[8], uint4 &hi, uint4 &mid, uint4 &lo) {
-    uint16_t h[8], m[8], l[8];
+// 8 fp32 values -> the 16-byte chunks of the NSPLIT activation planes at index dst
+__device__ __forceinline__ void split_store(const float (&x)[8], uint4 *planes, size_t dst, long plane_stride) {
+    uint16_t h[8], l[8];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) split3(x[e], h[e], m[e], l[e]);
-    hi = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
-    mid = make_uint4(pack2(m[0], m[1]), pack2(m[2], m[3]), pack2(m[4], m[5]), pack2(m[6], m[7]));
-    lo = make_uint4(pack2(l[0], l[1]), pack2(l[2], l[3]), pack2(l[4], l[5]), pack2(l[6], l[7]));
+    for (int e = 0; e < 8; ++e) split2(x[e], h[e], l[e]);
+    planes[dst] = make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
+    planes[dst + plane_stride] = make_uint4(pack2(l[0], l[1]), pack2(l[2], l[3]), pack2(l[4], l[5]), pack2(l[6], l[7]));
 }
 
 __device__ __forceinline__ void unpack_bf16x8(const uint4 &u, float (&x)[8]) {
@@ -160,6 +168,16 @@ __device__ __forceinline__ void unpack_bf16x8(const uint4 &u, float (&x)[8]) {
         x[2 * e] = bf16_to_f32((uint16_t)(w[e] & 0xFFFFu));
         x[2 * e + 1] = bf16_to_f32((uint16_t)(w[e] >> 16));
     }
+}
+
+// 8 bf16 values -> the same values as fp16 (one plane; exact inside fp16's normal range)
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4 &u) {
+    float x[8];
+    unpack_bf16x8(u, x);
+    uint16_t h[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) h[e] = f32_to_f16_bits(x[e]);
+    return make_uint4(pack2(h[0], h[1]), pack2(h[2], h[3]), pack2(h[4], h[5]), pack2(h[6], h[7]));
 }
 
 // Sum over the k-split partial buffers of the 8 floats at `off` (same order for any batching:
@@ -201,7 +219,7 @@ hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st);
 size_t lm_persist_lds_bytes();
 hipError_t lm_persist_configure();    // once per device
 
-hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, hipStream_t st);
+hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *dst, bool to_f16, hipStream_t st);
 hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb,
                               int M, int d, bool from_h, hipStream_t st);
 hipError_t launch_gather_e(const uint16_t *E, const int32_t *cond_tok, uint4 *xe, int nIb, int B, int L,

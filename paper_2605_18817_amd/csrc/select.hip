@@ -264,7 +264,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
         tokc = tokc < 0 ? 0 : (tokc >= a.V ? a.V - 1 : tokc);
         const uint4 *erow = reinterpret_cast<const uint4 *>(a.E + (size_t)tokc * a.d);
         for (int c8 = threadIdx.x; c8 < C8; c8 += 256) {
-            const uint4 v = erow[c8];
+            const uint4 v = bf16x8_to_f16x8(erow[c8]);   // the head body's operands are fp16
             for (int p = 0; p < L; ++p) a.xe[act_chunk_index(b * L + p, c8, a.nIb)] = v;
         }
     }

@@ -28,7 +28,16 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));  // native vector: stays in registers
 
-__device__ __forceinline__ bf16x8 as_frag(const u32x4 &u) { return __builtin_bit_cast(bf16x8, u); }
+// One 32x32x16 matrix multiply-accumulate on 16-byte operand fragments: the partial-sum GEMMs of the
+// head body take fp16 operands (weights converted at pack time, activations as fp16 planes), the LM
+// head bf16 ones.
+template <int EPI>
+__device__ __forceinline__ f32x16 mma_frag(const u32x4 &w, const u32x4 &x, const f32x16 &c) {
+    if constexpr (EPI == EPI_PARTIAL)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, x), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), c, 0, 0, 0);
+}
 
 template <int IT, int EPI, bool VEC4>
 __device__ __forceinline__ void stream_gemm_body(const StreamGemmArgs &a) {
@@ -150,13 +159,11 @@ __device__ __forceinline__ void stream_gemm_body(const StreamGemmArgs &a) {
             const u32x4 *cur = smem + buf * STAGE;
 #pragma unroll
             for (int j = 0; j < KSTEP; ++j) {
-                bf16x8 bfr[IT];
+                u32x4 bfr[IT];
 #pragma unroll
-                for (int it = 0; it < IT; ++it) bfr[it] = as_frag(cur[(j * IT + it) * 64 + lane]);
+                for (int it = 0; it < IT; ++it) bfr[it] = cur[(j * IT + it) * 64 + lane];
 #pragma unroll
-                for (int it = 0; it < IT; ++it)
-                    acc[it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(as_frag(wreg[PAR * KSTEP + j]),
-                                                                      bfr[it], acc[it], 0, 0, 0);
+                for (int it = 0; it < IT; ++it) acc[it] = mma_frag<EPI>(wreg[PAR * KSTEP + j], bfr[it], acc[it]);
             }
             if (p == np - 1 && g + 2 < g_end) {
 #pragma unroll

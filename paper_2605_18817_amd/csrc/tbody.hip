@@ -5,7 +5,7 @@
 //     o = attention of every block row over the sequence's prefix cache (bf16 keys / values) and
 //         the L rows of the block itself (no mask inside the block), grouped-query heads
 //     a = u + Wo o;  m = RMSNorm(a) g2;  u' = a + Wdown( SiLU(Wgate m) * (Wup m) )
-// The four projections run on the shared GEMM kernels (fp32 activations as three bf16 planes, fp32
+// The four projections run on the shared GEMM kernels (fp32 activations as two fp16 planes, fp32
 // partial sums); this file holds what sits between them: the residual-stream update with RMSNorm,
 // the gated activation, the rotary table and the attention kernel.  Everything here is fp32.
 #include "mrp_kernels.h"
@@ -39,7 +39,7 @@ __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t *__restri
 constexpr int NORM_MAX_CHUNKS = 4;  // per thread: d <= 8 * 256 * 4 = 8192
 
 // One workgroup per row: x = (resid ? resid : 0) + sum of partials; stream <- x;
-// planes <- split3(RMSNorm(x) gain).
+// planes <- split2(RMSNorm(x) gain).
 __global__ __launch_bounds__(256) void resid_norm_split_kernel(const float *__restrict__ part, int nKs,
                                                                const float *resid, float *stream,
                                                                const uint16_t *__restrict__ gain, float eps,
@@ -85,12 +85,7 @@ __global__ __launch_bounds__(256) void resid_norm_split_kernel(const float *__re
             unpack_bf16x8(*reinterpret_cast<const uint4 *>(gain + 8 * c8), g);
 #pragma unroll
             for (int e = 0; e < 8; ++e) y[e] = x[n][e] * inv * g[e];
-            uint4 hi, mid, lo;
-            split_chunk(y, hi, mid, lo);
-            const size_t dst = act_chunk_index(i, c8, nIb);
-            planes[dst] = hi;
-            planes[dst + plane_stride] = mid;
-            planes[dst + 2 * plane_stride] = lo;
+            split_store(y, planes, act_chunk_index(i, c8, nIb), plane_stride);
         }
     }
 }
@@ -106,12 +101,7 @@ __global__ __launch_bounds__(256) void swiglu_split_kernel(const float *__restri
     sum_partials(part, (size_t)M * 2 * ff, nKs, (size_t)i * 2 * ff + ff + 8 * c8, u);
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = g[e] / (1.0f + expf(-g[e])) * u[e];
-    uint4 hi, mid, lo;
-    split_chunk(x, hi, mid, lo);
-    const size_t dst = act_chunk_index(i, c8, nIb);
-    planes[dst] = hi;
-    planes[dst + plane_stride] = mid;
-    planes[dst + 2 * plane_stride] = lo;
+    split_store(x, planes, act_chunk_index(i, c8, nIb), plane_stride);
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -128,7 +118,7 @@ struct AttnArgs {
     const uint16_t *kc, *vc; // [B][P_max][nkv][HD] bf16
     const int32_t *prefix_len;
     int P_max, nh, nkv, L;
-    uint4 *o_planes;         // attention output, columns head * HD + e, as three bf16 planes
+    uint4 *o_planes;         // attention output, columns head * HD + e, as the activation planes of the next GEMM
     long plane_stride;
     int nIb;
 };
@@ -355,7 +345,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     }
     __syncthreads();
 
-    // ---- normalise, stage as [query][dimension], write the three planes
+    // ---- normalise, stage as [query][dimension], write the activation planes
 #pragma unroll
     for (int q = 0; q < QP; ++q) {
         const float inv_l = 1.0f / run_l[qg * QP + q];
@@ -369,12 +359,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         float x[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) x[e] = S[qq][8 * c + e];
-        uint4 hi, mid, lo;
-        split_chunk(x, hi, mid, lo);
-        const size_t dst = act_chunk_index(row, (g * rep + hrep) * (HD / 8) + c, a.nIb);
-        a.o_planes[dst] = hi;
-        a.o_planes[dst + a.plane_stride] = mid;
-        a.o_planes[dst + 2 * a.plane_stride] = lo;
+        split_store(x, a.o_planes, act_chunk_index(row, (g * rep + hrep) * (HD / 8) + c, a.nIb), a.plane_stride);
     }
 }
 

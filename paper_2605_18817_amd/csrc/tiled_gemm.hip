@@ -31,7 +31,16 @@ namespace {
 
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));   // native vector: arrays of it stay in registers
-__device__ __forceinline__ bf16x8 as_frag(const u32x4 &u) { return __builtin_bit_cast(bf16x8, u); }
+// One 32x32x16 matrix multiply-accumulate on 16-byte operand fragments: the partial-sum GEMMs of the
+// head body take fp16 operands (weights converted at pack time, activations as fp16 planes), the LM
+// head bf16 ones.
+template <int EPI>
+__device__ __forceinline__ f32x16 mma_frag(const u32x4 &w, const u32x4 &x, const f32x16 &c) {
+    if constexpr (EPI == EPI_PARTIAL)
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, x), c, 0, 0, 0);
+    else
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), c, 0, 0, 0);
+}
 
 constexpr int TG_KB = 4;                    // 16-wide k blocks per step (64 k)
 constexpr int TG_B = TG_KB * 8 * 64;        // u32x4 of an activation stage (256 rows x 64 k)
@@ -150,7 +159,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // activation fragments are double-buffered: the LDS reads of the next k block are issued
     // among the MFMAs of the current one (one wave per SIMD: nothing else hides them)
-    bf16x8 bf[2][8];
+    u32x4 bf[2][8];
 
     // Logit tile of the epilogue (EPI_LM): 8 slices of 32 activation rows x this wave's 64 vocabulary
     // entries, 8 16-byte pieces per lane each.  A piece is always fetched (addresses clamped into
@@ -184,7 +193,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         constexpr bool live = true;
         {
 #pragma unroll
-            for (int ib = 0; ib < 8; ++ib) bf[0][ib] = as_frag(cur[ib * 64 + lane]);
+            for (int ib = 0; ib < 8; ++ib) bf[0][ib] = cur[ib * 64 + lane];
         }
 #pragma unroll
         for (int kb = 0; kb < TG_KB; ++kb) {
@@ -213,15 +222,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 }
                 if (live) {
                     if (kb + 1 < TG_KB) {
-                        bf[(kb + 1) & 1][2 * g4] = as_frag(cur[((kb + 1) * 8 + 2 * g4) * 64 + lane]);
-                        bf[(kb + 1) & 1][2 * g4 + 1] = as_frag(cur[((kb + 1) * 8 + 2 * g4 + 1) * 64 + lane]);
+                        bf[(kb + 1) & 1][2 * g4] = cur[((kb + 1) * 8 + 2 * g4) * 64 + lane];
+                        bf[(kb + 1) & 1][2 * g4 + 1] = cur[((kb + 1) * 8 + 2 * g4 + 1) * 64 + lane];
                     }
                     __builtin_amdgcn_sched_barrier(0);
                     const int v2 = g4 >> 1, i0 = (g4 & 1) * 4;
 #pragma unroll
                     for (int it = 0; it < 4; ++it)
-                        acc[v2][i0 + it] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            as_frag(areg[PAR][v2][kb]), bf[kb & 1][i0 + it], acc[v2][i0 + it], 0, 0, 0);
+                        acc[v2][i0 + it] = mma_frag<EPI>(areg[PAR][v2][kb], bf[kb & 1][i0 + it], acc[v2][i0 + it]);
                 }
                 if (c == 0 && role == 0) {   // behind the first MFMAs: where the operands of the step after next are
                     cursor_get(kbw_n, bp_n);

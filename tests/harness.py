@@ -58,7 +58,8 @@ class Problem:
         del w_d
         dh = []
         for (w1, w2, g) in hs:
-            dh.append(mrp.Head(mrp.pack_weight(dev_bits(w1)), mrp.pack_weight(dev_bits(w2)), dev_bits(g)))
+            dh.append(mrp.Head(mrp.pack_weight(dev_bits(w1), body=True), mrp.pack_weight(dev_bits(w2), body=True),
+                               dev_bits(g)))
         self.heads_d = [dh[0]] * cfg.K if share_heads else dh
         torch.cuda.synchronize()
 

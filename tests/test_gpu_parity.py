@@ -45,6 +45,22 @@ def test_pack_weight_layout():
         np.testing.assert_array_equal(out, ref)
 
 
+def test_pack_body_weight_converts_to_fp16():
+    """Head-body weights: same block layout, every bf16 value as the nearest fp16 (exact in fp16's
+    normal range, subnormal below 6.1e-5)."""
+    rng = np.random.default_rng(4)
+    rows, cols = 70, 48
+    vals = rng.normal(0, 0.02, (rows, cols)).astype(np.float32)
+    vals[0, :8] = [0.0, 1.0, -2.5, 3e-5, -1e-6, 6.1e-5, 1000.0, -0.0]
+    w = mi.f32_to_bf16_bits(vals)
+    out = mrp.pack_weight(dev_bits(w), body=True).cpu().numpy().view(np.uint16)
+    rpad = (rows + 31) // 32 * 32
+    want = np.zeros((rpad, cols), np.uint16)
+    want[:rows] = mi.bf16_bits_to_f32(w).astype(np.float16).view(np.uint16)
+    ref = want.reshape(rpad // 32, 32, cols // 16, 2, 8).transpose(0, 2, 3, 1, 4).reshape(-1)
+    np.testing.assert_array_equal(out, ref)
+
+
 def test_config0_tiny():
     cfg = mi.config(0)
     prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=cfg.tau))

@@ -39,13 +39,13 @@ class TfProblem:
             key = id(self.heads[k][0])
             if key not in dev_heads:
                 w1, _, g = self.heads[k]
-                dev_heads[key] = mrp.Head(mrp.pack_weight(dev_bits(w1)), None, dev_bits(g))
+                dev_heads[key] = mrp.Head(mrp.pack_weight(dev_bits(w1), body=True), None, dev_bits(g))
                 ls = []
                 for lay in self.layers[k]:
                     kc = dev_bits(lay["kc"]) if td.P_max > 0 else None
                     vc = dev_bits(lay["vc"]) if td.P_max > 0 else None
-                    ls.append(mrp.TLayer(mrp.pack_weight(dev_bits(lay["Wqkv"])), mrp.pack_weight(dev_bits(lay["Wo"])),
-                                         mrp.pack_weight(dev_bits(lay["Wgu"])), mrp.pack_weight(dev_bits(lay["Wdown"])),
+                    pk = lambda a: mrp.pack_weight(dev_bits(a), body=True)
+                    ls.append(mrp.TLayer(pk(lay["Wqkv"]), pk(lay["Wo"]), pk(lay["Wgu"]), pk(lay["Wdown"]),
                                          dev_bits(lay["g1"]), dev_bits(lay["g2"]), kc, vc))
                 dev_layers[key] = ls
             self.heads_d.append(dev_heads[key])
