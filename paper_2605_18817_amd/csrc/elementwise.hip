@@ -1,5 +1,5 @@
 // Small per-row kernels around the stream GEMM: weight packing, activation
-// packing (with the exact 3-term bf16 split of fp32 activations), the SiLU
+// packing (with the two-term fp16 split of fp32 activations), the SiLU
 // between the head's two linear layers, and the RMSNorm that produces the bf16
 // LM-head operand together with the hidden-state carry h <- h + Delta
 // (paper Algorithm 2, inner loop).

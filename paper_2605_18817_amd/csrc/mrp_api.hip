@@ -38,7 +38,7 @@ struct mrp_ctx {
     mrp_tbody_dims tb;
     char *tb_ws;
     float *tb_U;               // residual stream [max_rows][d]
-    uint4 *tb_P;               // three activation planes, tb_plane uint4 each (widest of d, nh*hd, d_ff columns)
+    uint4 *tb_P;               // NSPLIT activation planes, tb_plane uint4 each (widest of d, nh*hd, d_ff columns)
     long tb_plane;
     float *tb_part;            // partial sums, tb_part_floats floats
     size_t tb_part_floats;

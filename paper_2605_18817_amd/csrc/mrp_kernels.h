@@ -26,7 +26,7 @@ constexpr int WG_WAVES = 4;       // wavefronts per workgroup of the stream GEMM
 constexpr int WG_ROWS = 32 * WG_WAVES;  // weight rows per workgroup tile
 
 // One K segment of the activation operand of the stream GEMM.  The operand is
-// the sum over `nplanes` packed bf16 planes; plane p of local k block kb, row
+// the sum over `nplanes` packed 16-bit planes (fp16 for the head body, bf16 for the LM head); plane p of local k block kb, row
 // block ib lives at base + p * plane_stride + (kb * nIb + ib) * 64 (uint4 units).
 struct ActSeg {
     const uint4 *base;

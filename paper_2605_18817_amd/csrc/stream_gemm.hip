@@ -1,7 +1,7 @@
-// Weight-streaming bf16 MFMA GEMM for gfx950:  out[i][r] (+)= sum_k W[r][k] * X[i][k].
+// Weight-streaming MFMA GEMM for gfx950 (bf16 operands for the LM head, fp16 for the head body):  out[i][r] (+)= sum_k W[r][k] * X[i][k].
 //
 // W is a packed weight matrix (32x16 fragment blocks, contiguous along k for a
-// 32-row block), X a packed activation operand made of one or more bf16 planes.
+// 32-row block), X a packed activation operand made of one or more 16-bit planes.
 // Each wavefront owns 32 weight rows and streams their fragments straight from
 // HBM into registers (one contiguous 1 KiB read per 16 k), never through LDS;
 // the activation slice of the current k range is shared by the four waves of a

@@ -1,4 +1,4 @@
-// Tiled bf16 MFMA GEMM for many activation rows (the MFMA-bound regime of the MRP
+// Tiled MFMA GEMM (bf16 operands for the LM head, fp16 for the head body) for many activation rows (the MFMA-bound regime of the MRP
 // chain):  out[i][r] (+)= sum_k W[r][k] * X[i][k]  with 256 x 256 output tiles.
 //
 // A workgroup of four wavefronts computes a tile of 256 weight rows x 256 activation rows;
