@@ -7,7 +7,8 @@
 //     a = u + Wo o;  m = RMSNorm(a) g2;  u' = a + Wdown( SiLU(Wgate m) * (Wup m) )
 // The four projections run on the shared GEMM kernels (fp32 activations as two fp16 planes, fp32
 // partial sums); this file holds what sits between them: the residual-stream update with RMSNorm,
-// the gated activation, the rotary table and the attention kernel.  Everything here is fp32.
+// the gated activation, the rotary table and the attention kernel (fp32 on the vector ALU, and the
+// matrix cores with two-term fp16 operands for the two contractions over the prefix cache).
 #include "mrp_kernels.h"
 
 namespace mrp {
@@ -15,10 +16,8 @@ namespace mrp {
 namespace {
 
 constexpr int HD = 128;   // head dimension (fixed)
-constexpr int TK = 128;   // prefix keys per tile
 constexpr int LB = 16;    // largest block length the attention kernel stages
 constexpr int KROW = HD + 8;   // padded key row in LDS (272 bytes)
-constexpr int SROW = TK + 4;   // padded score row: queries a wave works on side by side fall on different banks
 
 inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
@@ -105,11 +104,18 @@ __global__ __launch_bounds__(256) void swiglu_split_kernel(const float *__restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// Attention.  One workgroup per (kv head g, sequence b): its Q = (nh / nkv) * L query vectors
-// (query qq = hrep * L + i: head g * rep + hrep, block row i) share the keys and values of head g.
-// Keys arrive in tiles (TK prefix positions from the bf16 cache, then the block's own L rows in
-// fp32); per tile: scores -> LDS, online softmax per query (running max / sum, rescale factor),
-// then the value sum.
+// Attention.  One workgroup (4 wavefronts) per (kv head g, sequence b): its Q = (nh / nkv) * L query
+// vectors (query qq = hrep * L + i: head g * rep + hrep, block row i) share the keys and values of
+// head g.  The block's own L keys and values (fp32, from the projection) are handled first on the
+// vector ALU; the prefix cache then arrives in tiles of TK positions, requested one tile ahead and
+// parked in LDS as fp16, and both contractions of a tile run on the matrix cores with fp32-accurate
+// operands (the same two-term fp16 split as the head body's GEMMs):
+//   scores  S^T[key][q]  = K[key][:] . (q_hi + q_lo)[q][:]        A = keys,      B = query planes
+//   values  o^T[dim][q] += V^T[dim][key] (p_hi + p_lo)[q][key]    A = values^T,  B = probability planes
+// so in both a lane's 16 accumulators belong to ONE query (column lane % 32).  Between them an online
+// softmax per tile (running max / sum per query, rescale factor) in LDS.  Queries are scaled by
+// 2^6 / sqrt(HD) and probabilities by 2^14 before the split so that the low terms stay normal fp16
+// numbers; both powers of two are taken out again exactly.
 struct AttnArgs {
     const float *qkv;        // partial sums [nKs][M][ldq] of the q | k | v projection
     size_t split_stride;
@@ -122,6 +128,9 @@ struct AttnArgs {
     long plane_stride;
     int nIb;
 };
+
+constexpr float Q_SCALE = 64.f;        // 2^6
+constexpr float P_SCALE = 16384.f;     // 2^14
 
 // sum over the k splits of one projection output, in split order; eight loads in flight at a time
 __device__ __forceinline__ float sum_col(const AttnArgs &a, size_t off) {
@@ -136,12 +145,37 @@ __device__ __forceinline__ float sum_col(const AttnArgs &a, size_t off) {
     return x;
 }
 
-// softmax bookkeeping of one tile: S[qq][0 .. ncols) holds raw scores (-inf = no key) and is
-// replaced by exp(score - new running max); 256 / NQ adjacent lanes share a query, lane `part`
-// taking columns part, part + TPQ, ...
-template <int NQ>
-__device__ __forceinline__ void softmax_tile(float (*S)[SROW], float *run_m, float *run_l, float *rescale, int ncols) {
-    constexpr int TPQ = 256 / NQ;   // 4 .. 32 lanes per query, inside one wave
+__device__ __forceinline__ f32x16 mma_f16(const uint4 &x, const uint4 &y, const f32x16 &c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, x), __builtin_bit_cast(f16x8, y), c, 0, 0, 0);
+}
+
+// row of a 32 x 32 accumulator tile held in element r of lane `lane`
+__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+
+// LDS carve-up of the attention kernel (NQ query slots, TK keys per tile); offsets in bytes
+template <int NQ, int TK>
+struct AttnLds {
+    static constexpr int SROW = TK + 4;     // fp32 score row (padded)
+    static constexpr int PROW = TK + 8;     // fp16 probability row (padded: 16-byte reads hit every bank once per 16 lanes)
+    static constexpr size_t qs = 0;                                                // float [NQ][HD]
+    static constexpr size_t kb = qs + sizeof(float) * NQ * HD;                     // float [LB][HD]
+    static constexpr size_t vb = kb + sizeof(float) * LB * HD;                     // float [LB][HD]
+    static constexpr size_t S = vb + sizeof(float) * LB * HD;                      // float [NQ][SROW]
+    static constexpr size_t stat = S + sizeof(float) * NQ * SROW;                  // float [3][NQ]
+    static constexpr size_t qp = stat + sizeof(float) * 3 * NQ;                    // half [2][NQ][KROW]
+    static constexpr size_t pp = qp + sizeof(uint16_t) * 2 * NQ * KROW;            // half [2][NQ][PROW]
+    static constexpr size_t kt = pp + sizeof(uint16_t) * 2 * NQ * PROW;            // half [TK][KROW]
+    static constexpr size_t vt = kt + sizeof(uint16_t) * TK * KROW;                // half [TK][HD]
+    static constexpr size_t total = vt + sizeof(uint16_t) * TK * HD;
+};
+
+// softmax bookkeeping of one tile: S[qq][0 .. ncols) holds raw scores (-inf = no key); 256 / NQ
+// adjacent lanes share a query, lane `part` taking columns part, part + TPQ, ...  PLANES: the
+// probabilities exp(score - new max) go to the two fp16 planes (scaled by P_SCALE); else back to S.
+template <int NQ, int SROW, int PROW, bool PLANES>
+__device__ __forceinline__ void softmax_tile(float (*S)[SROW], uint16_t (*p_hi)[PROW], uint16_t (*p_lo)[PROW],
+                                             float *run_m, float *run_l, float *rescale, int ncols) {
+    constexpr int TPQ = 256 / NQ;   // 4 or 8 lanes per query, inside one wave
     const int qq = threadIdx.x / TPQ, part = threadIdx.x % TPQ;
     float mx = -INFINITY;
     for (int c = part; c < ncols; c += TPQ) mx = fmaxf(mx, S[qq][c]);
@@ -151,9 +185,16 @@ __device__ __forceinline__ void softmax_tile(float (*S)[SROW], float *run_m, flo
     const float m_new = fmaxf(m_old, mx);   // finite: every tile holds at least one key
     float sum = 0.f;
     for (int c = part; c < ncols; c += TPQ) {
-        const float p = __expf(S[qq][c] - m_new);   // exp(-inf) = 0 for absent keys
-        S[qq][c] = p;
-        sum += p;
+        const float pr = __expf(S[qq][c] - m_new);   // exp(-inf) = 0 for absent keys
+        if constexpr (PLANES) {
+            uint16_t hi, lo;
+            split2(pr * P_SCALE, hi, lo);
+            p_hi[qq][c] = hi;
+            p_lo[qq][c] = lo;
+        } else {
+            S[qq][c] = pr;
+        }
+        sum += pr;
     }
 #pragma unroll
     for (int off = TPQ / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
@@ -165,35 +206,42 @@ __device__ __forceinline__ void softmax_tile(float (*S)[SROW], float *run_m, flo
     }
 }
 
-template <int QP>
+// NQB: blocks of 32 query slots (1 or 2); TK: prefix keys per tile (128 for NQB = 1, 64 for NQB = 2)
+template <int NQB, int TK>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
-    constexpr int NQ = 8 * QP;   // query slots (Q <= NQ; unused slots hold zeros)
-    extern __shared__ float smem[];
-    float (*qs)[HD] = reinterpret_cast<float (*)[HD]>(smem);                       // [NQ][HD] rotated, scaled
-    float (*kb)[HD] = reinterpret_cast<float (*)[HD]>(smem + NQ * HD);             // [LB][HD] rotated block keys
-    float (*vb)[HD] = reinterpret_cast<float (*)[HD]>(smem + (NQ + LB) * HD);      // [LB][HD] block values
-    float (*S)[SROW] = reinterpret_cast<float (*)[SROW]>(smem + (NQ + 2 * LB) * HD);   // [NQ][TK] (padded rows)
-    float *run_m = smem + (NQ + 2 * LB) * HD + NQ * SROW;
+    constexpr int NQ = 32 * NQB;
+    using Lds = AttnLds<NQ, TK>;
+    constexpr int SROW = Lds::SROW, PROW = Lds::PROW;
+    constexpr int KBLK = TK / 32;                // key blocks of a tile
+    static_assert(KBLK * NQB == 4, "one (key block, query block) pair per wavefront");
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
+    float (*qs)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::qs);       // rotated, scaled queries (fp32)
+    float (*kb)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::kb);       // rotated block keys
+    float (*vb)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::vb);       // block values
+    float (*S)[SROW] = reinterpret_cast<float (*)[SROW]>(smem_raw + Lds::S);
+    float *run_m = reinterpret_cast<float *>(smem_raw + Lds::stat);
     float *run_l = run_m + NQ;
     float *rescale = run_l + NQ;
-    // the current prefix tile: keys with rows padded to KROW entries (a lane reading its own key row
-    // 16 bytes at a time then hits every LDS bank once per 16 lanes), values unpadded
-    uint16_t (*kt)[KROW] = reinterpret_cast<uint16_t (*)[KROW]>(rescale + NQ);
-    uint16_t (*vt)[HD] = reinterpret_cast<uint16_t (*)[HD]>(reinterpret_cast<uint16_t *>(rescale + NQ) + TK * KROW);
+    uint16_t (*qp)[NQ][KROW] = reinterpret_cast<uint16_t (*)[NQ][KROW]>(smem_raw + Lds::qp);   // [2] query planes
+    uint16_t (*pp)[NQ][PROW] = reinterpret_cast<uint16_t (*)[NQ][PROW]>(smem_raw + Lds::pp);   // [2] probability planes
+    uint16_t (*kt)[KROW] = reinterpret_cast<uint16_t (*)[KROW]>(smem_raw + Lds::kt);           // tile keys (fp16)
+    uint16_t (*vt)[HD] = reinterpret_cast<uint16_t (*)[HD]>(smem_raw + Lds::vt);               // tile values (fp16)
 
     const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
     const int L = a.L, rep = a.nh / a.nkv, Q = rep * L;
     const int qd = a.nh * HD, kvd = a.nkv * HD;
     int P = a.prefix_len[b];
     P = P < 0 ? 0 : (P > a.P_max ? a.P_max : P);
     const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
 
-    // ---- prefix tiles: a tile's keys and values are requested (16 bytes per lane, whole cache rows)
-    // while the previous tile is being worked on, then parked in LDS
-    uint4 kreg[TK * HD / 8 / 256], vreg[TK * HD / 8 / 256];
+    // a tile's keys and values are requested (16 bytes per lane, whole cache rows) while the previous
+    // tile is being worked on
+    constexpr int NREQ = TK * HD / 8 / 256;
+    uint4 kreg[NREQ], vreg[NREQ];
     auto request = [&](int t0) {
 #pragma unroll
-        for (int n = 0; n < TK * HD / 8 / 256; ++n) {
+        for (int n = 0; n < NREQ; ++n) {
             const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
             const int t = t0 + key;
             kreg[n] = make_uint4(0, 0, 0, 0);
@@ -207,7 +255,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     };
     if (P > 0) request(0);
 
-    // ---- prologue: the block's q (rotated, scaled), k (rotated) and v for this kv head
+    // ---- prologue: the block's q (rotated, scaled; fp32 and as two fp16 planes), k (rotated) and v
     for (int idx = tid; idx < NQ * (HD / 2); idx += 256) {
         const int qq = idx / (HD / 2), j = idx % (HD / 2);
         float r0 = 0.f, r1 = 0.f;
@@ -221,6 +269,11 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         }
         qs[qq][j] = r0;
         qs[qq][j + HD / 2] = r1;
+        uint16_t hi, lo;
+        split2(r0 * Q_SCALE, hi, lo);
+        qp[0][qq][j] = hi; qp[1][qq][j] = lo;
+        split2(r1 * Q_SCALE, hi, lo);
+        qp[0][qq][j + HD / 2] = hi; qp[1][qq][j + HD / 2] = lo;
     }
     for (int idx = tid; idx < L * (HD / 2); idx += 256) {
         const int i = idx / (HD / 2), j = idx % (HD / 2), row = b * L + i;
@@ -237,86 +290,15 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     if (tid < NQ) { run_m[tid] = -INFINITY; run_l[tid] = 0.f; rescale[tid] = 0.f; }
     __syncthreads();
 
-    // register tiles: a thread works on 4 keys x QP queries (scores) and 4 dimensions x QP queries
-    // (values), so that one LDS read feeds four multiply-adds per query
-    const int lg = tid & 31, qg = tid >> 5;   // key group / dimension group, query group
-    float o[QP][4];
+    // Output accumulators: wave w owns dimensions 32 w .. 32 w + 31; element r of lane `lane` is
+    // o[query 32 qb + lane % 32][dimension 32 w + acc_row(r, lane)], in units of P_SCALE.
+    f32x16 o_acc[NQB];
 #pragma unroll
-    for (int q = 0; q < QP; ++q)
+    for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
-        for (int dd = 0; dd < 4; ++dd) o[q][dd] = 0.f;
+        for (int r = 0; r < 16; ++r) o_acc[qb][r] = 0.f;
 
-    for (int t0 = 0; t0 < P; t0 += TK) {
-#pragma unroll
-        for (int n = 0; n < TK * HD / 8 / 256; ++n) {
-            const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
-            *reinterpret_cast<uint4 *>(&kt[key][8 * c]) = kreg[n];
-            *reinterpret_cast<uint4 *>(&vt[key][8 * c]) = vreg[n];
-        }
-        __syncthreads();
-        if (t0 + TK < P) request(t0 + TK);
-        {   // scores of keys lg, lg + 32, lg + 64, lg + 96 of the tile
-            float acc[QP][4];
-#pragma unroll
-            for (int q = 0; q < QP; ++q)
-#pragma unroll
-                for (int u = 0; u < 4; ++u) acc[q][u] = 0.f;
-            if (t0 + lg < P) {
-#pragma unroll 2
-                for (int c = 0; c < HD / 8; ++c) {
-                    float kf[4][8];
-#pragma unroll
-                    for (int u = 0; u < 4; ++u)
-                        unpack_bf16x8(*reinterpret_cast<const uint4 *>(&kt[lg + 32 * u][8 * c]), kf[u]);
-#pragma unroll
-                    for (int q = 0; q < QP; ++q) {
-                        const float4 q0 = *reinterpret_cast<const float4 *>(&qs[qg * QP + q][8 * c]);
-                        const float4 q1 = *reinterpret_cast<const float4 *>(&qs[qg * QP + q][8 * c + 4]);
-#pragma unroll
-                        for (int u = 0; u < 4; ++u)
-                            acc[q][u] += q0.x * kf[u][0] + q0.y * kf[u][1] + q0.z * kf[u][2] + q0.w * kf[u][3] +
-                                         q1.x * kf[u][4] + q1.y * kf[u][5] + q1.z * kf[u][6] + q1.w * kf[u][7];
-                    }
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < QP; ++q)
-#pragma unroll
-                for (int u = 0; u < 4; ++u)
-                    S[qg * QP + q][lg + 32 * u] = (t0 + lg + 32 * u < P) ? acc[q][u] : -INFINITY;
-        }
-        __syncthreads();
-        softmax_tile<NQ>(S, run_m, run_l, rescale, TK);
-        __syncthreads();
-        {   // values: dimensions 4 lg .. 4 lg + 3
-#pragma unroll
-            for (int q = 0; q < QP; ++q) {
-                const float f = rescale[qg * QP + q];
-#pragma unroll
-                for (int dd = 0; dd < 4; ++dd) o[q][dd] *= f;
-            }
-            const int nk = (P - t0 < TK) ? (P - t0) : TK;   // (absent keys: probability 0, value 0)
-            for (int k4 = 0; k4 < nk; k4 += 4) {
-                float v[4][4];
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const uint2 raw = *reinterpret_cast<const uint2 *>(&vt[k4 + u][4 * lg]);
-                    v[u][0] = __uint_as_float(raw.x << 16); v[u][1] = __uint_as_float(raw.x & 0xFFFF0000u);
-                    v[u][2] = __uint_as_float(raw.y << 16); v[u][3] = __uint_as_float(raw.y & 0xFFFF0000u);
-                }
-#pragma unroll
-                for (int q = 0; q < QP; ++q) {
-                    const float4 p = *reinterpret_cast<const float4 *>(&S[qg * QP + q][k4]);
-#pragma unroll
-                    for (int dd = 0; dd < 4; ++dd)
-                        o[q][dd] += p.x * v[0][dd] + p.y * v[1][dd] + p.z * v[2][dd] + p.w * v[3][dd];
-                }
-            }
-        }
-        __syncthreads();
-    }
-
-    // ---- the block's own rows (fp32 keys and values from LDS); 16 score columns, absent keys -inf
+    // ---- the block's own rows (fp32 keys and values, vector ALU); 16 score columns, absent keys -inf
     for (int qq = tid >> 4; qq < NQ; qq += 16) {
         const int key = tid & 15;
         float acc = -INFINITY;
@@ -327,30 +309,90 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         S[qq][key] = acc;
     }
     __syncthreads();
-    softmax_tile<NQ>(S, run_m, run_l, rescale, 16);
+    softmax_tile<NQ, SROW, PROW, false>(S, pp[0], pp[1], run_m, run_l, rescale, 16);
     __syncthreads();
-#pragma unroll
-    for (int q = 0; q < QP; ++q) {
-        const float f = rescale[qg * QP + q];
-#pragma unroll
-        for (int dd = 0; dd < 4; ++dd) o[q][dd] *= f;
-    }
     for (int k = 0; k < L; ++k) {
-        const float4 v = *reinterpret_cast<const float4 *>(&vb[k][4 * lg]);
 #pragma unroll
-        for (int q = 0; q < QP; ++q) {
-            const float pk = S[qg * QP + q][k];
-            o[q][0] += pk * v.x; o[q][1] += pk * v.y; o[q][2] += pk * v.z; o[q][3] += pk * v.w;
+        for (int qb = 0; qb < NQB; ++qb) {
+            const float pk = S[32 * qb + l32][k] * P_SCALE;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float4 v = *reinterpret_cast<const float4 *>(&vb[k][32 * wave + 8 * j + 4 * half]);
+                o_acc[qb][4 * j + 0] += pk * v.x; o_acc[qb][4 * j + 1] += pk * v.y;
+                o_acc[qb][4 * j + 2] += pk * v.z; o_acc[qb][4 * j + 3] += pk * v.w;
+            }
         }
     }
     __syncthreads();
 
-    // ---- normalise, stage as [query][dimension], write the activation planes
+    // ---- prefix tiles
+    const int kblk = wave % KBLK, sqb = wave / KBLK;   // this wave's (key block, query block) of the score phase
+    for (int t0 = 0; t0 < P; t0 += TK) {
 #pragma unroll
-    for (int q = 0; q < QP; ++q) {
-        const float inv_l = 1.0f / run_l[qg * QP + q];
-        *reinterpret_cast<float4 *>(&S[qg * QP + q][4 * lg]) =
-            make_float4(o[q][0] * inv_l, o[q][1] * inv_l, o[q][2] * inv_l, o[q][3] * inv_l);   // (TK == HD)
+        for (int n = 0; n < NREQ; ++n) {   // park the tile as fp16 (absent keys: zeros)
+            const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
+            *reinterpret_cast<uint4 *>(&kt[key][8 * c]) = bf16x8_to_f16x8(kreg[n]);
+            *reinterpret_cast<uint4 *>(&vt[key][8 * c]) = bf16x8_to_f16x8(vreg[n]);
+        }
+        __syncthreads();
+        if (t0 + TK < P) request(t0 + TK);
+        {   // scores: 32 keys x 32 queries per wave
+            f32x16 acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+            for (int ks = 0; ks < HD / 16; ++ks) {
+                const int col = 16 * ks + 8 * half;
+                const uint4 kf = *reinterpret_cast<const uint4 *>(&kt[32 * kblk + l32][col]);
+                const uint4 q_hi = *reinterpret_cast<const uint4 *>(&qp[0][32 * sqb + l32][col]);
+                const uint4 q_lo = *reinterpret_cast<const uint4 *>(&qp[1][32 * sqb + l32][col]);
+                acc = mma_f16(kf, q_hi, acc);
+                acc = mma_f16(kf, q_lo, acc);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int key = 32 * kblk + acc_row(r, lane);
+                S[32 * sqb + l32][key] = (t0 + key < P) ? acc[r] * (1.0f / Q_SCALE) : -INFINITY;
+            }
+        }
+        __syncthreads();
+        softmax_tile<NQ, SROW, PROW, true>(S, pp[0], pp[1], run_m, run_l, rescale, TK);
+        __syncthreads();
+        {   // values: 32 dimensions x all queries per wave
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb) {
+                const float f = rescale[32 * qb + l32];
+#pragma unroll
+                for (int r = 0; r < 16; ++r) o_acc[qb][r] *= f;
+            }
+#pragma unroll
+            for (int ks = 0; ks < TK / 16; ++ks) {
+                // V^T fragment: this lane's dimension, keys 16 ks + 8 half .. + 7
+                uint16_t vh[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) vh[e] = vt[16 * ks + 8 * half + e][32 * wave + l32];
+                const uint4 vf = make_uint4(pack2(vh[0], vh[1]), pack2(vh[2], vh[3]), pack2(vh[4], vh[5]), pack2(vh[6], vh[7]));
+#pragma unroll
+                for (int qb = 0; qb < NQB; ++qb) {
+                    const uint4 p_hi = *reinterpret_cast<const uint4 *>(&pp[0][32 * qb + l32][16 * ks + 8 * half]);
+                    const uint4 p_lo = *reinterpret_cast<const uint4 *>(&pp[1][32 * qb + l32][16 * ks + 8 * half]);
+                    o_acc[qb] = mma_f16(vf, p_hi, o_acc[qb]);
+                    o_acc[qb] = mma_f16(vf, p_lo, o_acc[qb]);
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- normalise, stage as [query][dimension] (the fp32 query buffer is free by now), write the planes
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        const float inv = 1.0f / (run_l[32 * qb + l32] * P_SCALE);
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            *reinterpret_cast<float4 *>(&qs[32 * qb + l32][32 * wave + 8 * j + 4 * half]) =
+                make_float4(o_acc[qb][4 * j] * inv, o_acc[qb][4 * j + 1] * inv, o_acc[qb][4 * j + 2] * inv,
+                            o_acc[qb][4 * j + 3] * inv);
     }
     __syncthreads();
     for (int idx = tid; idx < Q * (HD / 8); idx += 256) {
@@ -358,38 +400,29 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         const int hrep = qq / L, i = qq % L, row = b * L + i;
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = S[qq][8 * c + e];
+        for (int e = 0; e < 8; ++e) x[e] = qs[qq][8 * c + e];
         split_store(x, a.o_planes, act_chunk_index(row, (g * rep + hrep) * (HD / 8) + c, a.nIb), a.plane_stride);
     }
 }
 
-static_assert(TK == HD, "the score tile doubles as the output staging buffer");
-
-template <int QP>
-constexpr size_t attn_lds_bytes() {
-    return sizeof(float) * ((size_t)(8 * QP + 2 * LB) * HD + (size_t)8 * QP * SROW + 3 * 8 * QP) +
-           sizeof(uint16_t) * ((size_t)TK * KROW + (size_t)TK * HD);
-}
-
-template <int QP>
+template <int NQB, int TK>
 hipError_t attn_configure_one() {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<QP>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)attn_lds_bytes<QP>());
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<NQB, TK>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)AttnLds<32 * NQB, TK>::total);
 }
 
-template <int QP>
+template <int NQB, int TK>
 hipError_t attn_launch_one(const AttnArgs &a, int B, hipStream_t st) {
-    hipLaunchKernelGGL(attn_kernel<QP>, dim3(a.nkv, B), dim3(256), attn_lds_bytes<QP>(), st, a);
+    constexpr size_t lds = AttnLds<32 * NQB, TK>::total;
+    hipLaunchKernelGGL((attn_kernel<NQB, TK>), dim3(a.nkv, B), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t tbody_configure() {
-    hipError_t e = attn_configure_one<1>();
-    if (e == hipSuccess) e = attn_configure_one<2>();
-    if (e == hipSuccess) e = attn_configure_one<4>();
-    if (e == hipSuccess) e = attn_configure_one<8>();
+    hipError_t e = attn_configure_one<1, 128>();
+    if (e == hipSuccess) e = attn_configure_one<2, 64>();
     return e;
 }
 
@@ -433,10 +466,8 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
     a.P_max = P_max; a.nh = nh; a.nkv = nkv; a.L = L;
     a.o_planes = o_planes; a.plane_stride = plane_stride; a.nIb = nIb;
     const int Q = (nh / nkv) * L;
-    if (Q <= 8) return attn_launch_one<1>(a, B, st);
-    if (Q <= 16) return attn_launch_one<2>(a, B, st);
-    if (Q <= 32) return attn_launch_one<4>(a, B, st);
-    return attn_launch_one<8>(a, B, st);
+    if (Q <= 32) return attn_launch_one<1, 128>(a, B, st);
+    return attn_launch_one<2, 64>(a, B, st);
 }
 
 }  // namespace mrp
