@@ -33,6 +33,15 @@ def test_host_only_entry_points():
     assert lib.mrp_destroy(None) == -1
     h = ctypes.c_void_p()
     assert lib.mrp_create(ctypes.byref(h), None) == -1
+    # every other entry point refuses a NULL context (or NULL buffers) before anything is launched
+    assert lib.mrp_pack_body_weight(None, None, 32, 16, None) == -1
+    assert lib.mrp_tbody_create(None, None) == -1
+    assert lib.mrp_chain_step(None, None, 1, 0, None, None, None, None, None, None, None, None) == -1
+    assert lib.mrp_chain_step_tf(None, None, 1, 0, None, None, None, None, None, None, None, None, None, None) == -1
+    assert lib.mrp_kl_loss(None, None, 1, None, None, None, 1.0, None, None) == -1
+    assert lib.mrp_residual_rms(None, None, 1, 5, 64, None, 0, None, None) == -1
+    assert lib.mrp_commit(None, None, 1, None, None, None, None, None) == -1
+    assert lib.mrp_profile_enable(None, 1) == -1
 
 
 def test_no_cpu_fallback_without_gpu():
