@@ -106,16 +106,22 @@ __global__ __launch_bounds__(256) void swiglu_split_kernel(const float *__restri
 // ------------------------------------------------------------------------------------------------
 // Attention.  One workgroup (4 wavefronts) per (kv head g, sequence b): its Q = (nh / nkv) * L query
 // vectors (query qq = hrep * L + i: head g * rep + hrep, block row i) share the keys and values of
-// head g.  The block's own L keys and values (fp32, from the projection) are handled first on the
-// vector ALU; the prefix cache then arrives in tiles of TK positions, requested one tile ahead and
-// parked in LDS as fp16, and both contractions of a tile run on the matrix cores with fp32-accurate
-// operands (the same two-term fp16 split as the head body's GEMMs):
-//   scores  S^T[key][q]  = K[key][:] . (q_hi + q_lo)[q][:]        A = keys,      B = query planes
-//   values  o^T[dim][q] += V^T[dim][key] (p_hi + p_lo)[q][key]    A = values^T,  B = probability planes
-// so in both a lane's 16 accumulators belong to ONE query (column lane % 32).  Between them an online
-// softmax per tile (running max / sum per query, rescale factor) in LDS.  Queries are scaled by
-// 2^6 / sqrt(HD) and probabilities by 2^14 before the split so that the low terms stay normal fp16
-// numbers; both powers of two are taken out again exactly.
+// head g.
+//   * The block's own L keys and values (fp32, from the projection) are handled by the whole
+//     workgroup on the vector ALU.
+//   * The prefix cache is walked in chunks of 32 positions, chunk c by wavefront c % 4, and each
+//     wavefront runs its own online softmax over its chunks: no workgroup barrier inside the walk.
+//     Both contractions run on the matrix cores with fp32-accurate operands (the same two-term fp16
+//     split as the head body's GEMMs; the cache's bf16 values are converted to fp16):
+//       scores  S^T[key][q]  = K[key][:] . (q_hi + q_lo)[q][:]        A = keys,      B = query planes
+//       values  o^T[dim][q] += V^T[dim][key] (p_hi + p_lo)[q][key]    A = values^T,  B = probabilities
+//     In both a lane's 16 accumulators belong to ONE query (column lane % 32), so the chunk's maximum
+//     and sum per query need one exchange with lane ^ 32, and the lane's 16 probabilities are, as they
+//     stand, its two B fragments of the value product (the key order inside a chunk is immaterial as
+//     long as the value fragments are gathered in the same order).
+//   * At the end the five partial results per query (block, four wavefronts) are merged in a fixed order.
+// Queries are scaled by 2^6 / sqrt(HD) and probabilities by 2^14 before the split so that the low
+// terms stay normal fp16 numbers; both powers of two are taken out again exactly.
 struct AttnArgs {
     const float *qkv;        // partial sums [nKs][M][ldq] of the q | k | v projection
     size_t split_stride;
@@ -131,6 +137,8 @@ struct AttnArgs {
 
 constexpr float Q_SCALE = 64.f;        // 2^6
 constexpr float P_SCALE = 16384.f;     // 2^14
+constexpr int CK = 32;                 // prefix positions per chunk
+constexpr int SCOLS = 20;              // score columns of the block phase (16 + padding)
 
 // sum over the k splits of one projection output, in split order; eight loads in flight at a time
 __device__ __forceinline__ float sum_col(const AttnArgs &a, size_t off) {
@@ -149,83 +157,61 @@ __device__ __forceinline__ f32x16 mma_f16(const uint4 &x, const uint4 &y, const 
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, x), __builtin_bit_cast(f16x8, y), c, 0, 0, 0);
 }
 
-// row of a 32 x 32 accumulator tile held in element r of lane `lane`
-__device__ __forceinline__ int acc_row(int r, int lane) { return 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3); }
+// row of a 32 x 32 accumulator tile held in element r of a lane of half-wave `half`
+__device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
-// LDS carve-up of the attention kernel (NQ query slots, TK keys per tile); offsets in bytes
-template <int NQ, int TK>
+// LDS carve-up of the attention kernel (NQ query slots); offsets in bytes
+template <int NQ>
 struct AttnLds {
-    static constexpr int SROW = TK + 4;     // fp32 score row (padded)
-    static constexpr int PROW = TK + 8;     // fp16 probability row (padded: 16-byte reads hit every bank once per 16 lanes)
-    static constexpr size_t qs = 0;                                                // float [NQ][HD]
+    static constexpr size_t qs = 0;                                                // float [NQ][HD] (later: merged output)
     static constexpr size_t kb = qs + sizeof(float) * NQ * HD;                     // float [LB][HD]
     static constexpr size_t vb = kb + sizeof(float) * LB * HD;                     // float [LB][HD]
-    static constexpr size_t S = vb + sizeof(float) * LB * HD;                      // float [NQ][SROW]
-    static constexpr size_t stat = S + sizeof(float) * NQ * SROW;                  // float [3][NQ]
-    static constexpr size_t qp = stat + sizeof(float) * 3 * NQ;                    // half [2][NQ][KROW]
-    static constexpr size_t pp = qp + sizeof(uint16_t) * 2 * NQ * KROW;            // half [2][NQ][PROW]
-    static constexpr size_t kt = pp + sizeof(uint16_t) * 2 * NQ * PROW;            // half [TK][KROW]
-    static constexpr size_t vt = kt + sizeof(uint16_t) * TK * KROW;                // half [TK][HD]
-    static constexpr size_t total = vt + sizeof(uint16_t) * TK * HD;
+    static constexpr size_t S = vb + sizeof(float) * LB * HD;                      // float [NQ][SCOLS]
+    static constexpr size_t stat = S + sizeof(float) * NQ * SCOLS;                 // float [3][NQ] block max / sum / scratch
+    static constexpr size_t wstat = stat + sizeof(float) * 3 * NQ;                 // float [2][4][NQ] per-wave max / sum
+    static constexpr size_t qp = wstat + sizeof(float) * 8 * NQ;                   // half [2][NQ][KROW]
+    static constexpr size_t vch = qp + sizeof(uint16_t) * 2 * NQ * KROW;           // half [4][CK][KROW] per-wave value chunk
+    static constexpr size_t total = vch + sizeof(uint16_t) * 4 * CK * KROW;
 };
 
-// softmax bookkeeping of one tile: S[qq][0 .. ncols) holds raw scores (-inf = no key); 256 / NQ
-// adjacent lanes share a query, lane `part` taking columns part, part + TPQ, ...  PLANES: the
-// probabilities exp(score - new max) go to the two fp16 planes (scaled by P_SCALE); else back to S.
-template <int NQ, int SROW, int PROW, bool PLANES>
-__device__ __forceinline__ void softmax_tile(float (*S)[SROW], uint16_t (*p_hi)[PROW], uint16_t (*p_lo)[PROW],
-                                             float *run_m, float *run_l, float *rescale, int ncols) {
+// softmax of the block phase: S[qq][0 .. 16) holds raw scores (-inf = no key) and is replaced by
+// exp(score - max); 256 / NQ adjacent lanes share a query.
+template <int NQ>
+__device__ __forceinline__ void softmax_block(float (*S)[SCOLS], float *blk_m, float *blk_l) {
     constexpr int TPQ = 256 / NQ;   // 4 or 8 lanes per query, inside one wave
     const int qq = threadIdx.x / TPQ, part = threadIdx.x % TPQ;
     float mx = -INFINITY;
-    for (int c = part; c < ncols; c += TPQ) mx = fmaxf(mx, S[qq][c]);
+    for (int c = part; c < 16; c += TPQ) mx = fmaxf(mx, S[qq][c]);
 #pragma unroll
     for (int off = TPQ / 2; off > 0; off >>= 1) mx = fmaxf(mx, __shfl_xor(mx, off));
-    const float m_old = run_m[qq];
-    const float m_new = fmaxf(m_old, mx);   // finite: every tile holds at least one key
     float sum = 0.f;
-    for (int c = part; c < ncols; c += TPQ) {
-        const float pr = __expf(S[qq][c] - m_new);   // exp(-inf) = 0 for absent keys
-        if constexpr (PLANES) {
-            uint16_t hi, lo;
-            split2(pr * P_SCALE, hi, lo);
-            p_hi[qq][c] = hi;
-            p_lo[qq][c] = lo;
-        } else {
-            S[qq][c] = pr;
-        }
+    for (int c = part; c < 16; c += TPQ) {
+        const float pr = __expf(S[qq][c] - mx);   // exp(-inf) = 0 for absent keys; the block has at least one row
+        S[qq][c] = pr;
         sum += pr;
     }
 #pragma unroll
     for (int off = TPQ / 2; off > 0; off >>= 1) sum += __shfl_xor(sum, off);
-    if (part == 0) {
-        const float f = (m_old == -INFINITY) ? 0.f : __expf(m_old - m_new);
-        rescale[qq] = f;
-        run_m[qq] = m_new;
-        run_l[qq] = run_l[qq] * f + sum;
-    }
+    if (part == 0) { blk_m[qq] = mx; blk_l[qq] = sum; }
 }
 
-// NQB: blocks of 32 query slots (1 or 2); TK: prefix keys per tile (128 for NQB = 1, 64 for NQB = 2)
-template <int NQB, int TK>
+// NQB: blocks of 32 query slots (1 or 2)
+template <int NQB>
 __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     constexpr int NQ = 32 * NQB;
-    using Lds = AttnLds<NQ, TK>;
-    constexpr int SROW = Lds::SROW, PROW = Lds::PROW;
-    constexpr int KBLK = TK / 32;                // key blocks of a tile
-    static_assert(KBLK * NQB == 4, "one (key block, query block) pair per wavefront");
+    using Lds = AttnLds<NQ>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float (*qs)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::qs);       // rotated, scaled queries (fp32)
     float (*kb)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::kb);       // rotated block keys
     float (*vb)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::vb);       // block values
-    float (*S)[SROW] = reinterpret_cast<float (*)[SROW]>(smem_raw + Lds::S);
-    float *run_m = reinterpret_cast<float *>(smem_raw + Lds::stat);
-    float *run_l = run_m + NQ;
-    float *rescale = run_l + NQ;
+    float (*S)[SCOLS] = reinterpret_cast<float (*)[SCOLS]>(smem_raw + Lds::S);
+    float *blk_m = reinterpret_cast<float *>(smem_raw + Lds::stat);
+    float *blk_l = blk_m + NQ;
+    float *tot_l = blk_l + NQ;
+    float (*w_m)[NQ] = reinterpret_cast<float (*)[NQ]>(smem_raw + Lds::wstat);    // [4] per-wave running max
+    float (*w_l)[NQ] = w_m + 4;                                                   // [4] per-wave running sum
     uint16_t (*qp)[NQ][KROW] = reinterpret_cast<uint16_t (*)[NQ][KROW]>(smem_raw + Lds::qp);   // [2] query planes
-    uint16_t (*pp)[NQ][PROW] = reinterpret_cast<uint16_t (*)[NQ][PROW]>(smem_raw + Lds::pp);   // [2] probability planes
-    uint16_t (*kt)[KROW] = reinterpret_cast<uint16_t (*)[KROW]>(smem_raw + Lds::kt);           // tile keys (fp16)
-    uint16_t (*vt)[HD] = reinterpret_cast<uint16_t (*)[HD]>(smem_raw + Lds::vt);               // tile values (fp16)
+    uint16_t (*vch)[CK][KROW] = reinterpret_cast<uint16_t (*)[CK][KROW]>(smem_raw + Lds::vch); // [4] value chunks
 
     const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
@@ -234,26 +220,31 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     int P = a.prefix_len[b];
     P = P < 0 ? 0 : (P > a.P_max ? a.P_max : P);
     const float scale = 0.08838834764831845f;   // 1 / sqrt(128)
+    const int nchunks = (P + CK - 1) / CK;
 
-    // a tile's keys and values are requested (16 bytes per lane, whole cache rows) while the previous
-    // tile is being worked on
-    constexpr int NREQ = TK * HD / 8 / 256;
-    uint4 kreg[NREQ], vreg[NREQ];
-    auto request = [&](int t0) {
+    // A wave's next chunk is requested while it works on the current one.  Keys go straight into
+    // matrix-core A fragments (lane = key row, 16 bytes per 16 dimensions); values are fetched as
+    // whole rows (16 consecutive lanes per position) and parked in the wave's LDS chunk.
+    uint4 kreg[HD / 16], vreg[CK * HD / 8 / 64];
+    auto request = [&](int c) {
+        const int tk = c * CK + l32;
 #pragma unroll
-        for (int n = 0; n < NREQ; ++n) {
-            const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
-            const int t = t0 + key;
-            kreg[n] = make_uint4(0, 0, 0, 0);
+        for (int ks = 0; ks < HD / 16; ++ks) {
+            kreg[ks] = make_uint4(0, 0, 0, 0);
+            if (tk < P)
+                kreg[ks] = *reinterpret_cast<const uint4 *>(a.kc + (((size_t)b * a.P_max + tk) * a.nkv + g) * HD +
+                                                            16 * ks + 8 * half);
+        }
+#pragma unroll
+        for (int n = 0; n < CK * HD / 8 / 64; ++n) {
+            const int idx = lane + 64 * n, key = idx >> 4, c16 = idx & 15;
+            const int tv = c * CK + key;
             vreg[n] = make_uint4(0, 0, 0, 0);
-            if (t < P) {
-                const size_t off = (((size_t)b * a.P_max + t) * a.nkv + g) * HD + 8 * c;
-                kreg[n] = *reinterpret_cast<const uint4 *>(a.kc + off);
-                vreg[n] = *reinterpret_cast<const uint4 *>(a.vc + off);
-            }
+            if (tv < P)
+                vreg[n] = *reinterpret_cast<const uint4 *>(a.vc + (((size_t)b * a.P_max + tv) * a.nkv + g) * HD + 8 * c16);
         }
     };
-    if (P > 0) request(0);
+    if (wave < nchunks) request(wave);
 
     // ---- prologue: the block's q (rotated, scaled; fp32 and as two fp16 planes), k (rotated) and v
     for (int idx = tid; idx < NQ * (HD / 2); idx += 256) {
@@ -287,18 +278,11 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         const int i = idx / HD, e = idx % HD, row = b * L + i;
         vb[i][e] = sum_col(a, (size_t)row * a.ldq + qd + kvd + (size_t)g * HD + e);
     }
-    if (tid < NQ) { run_m[tid] = -INFINITY; run_l[tid] = 0.f; rescale[tid] = 0.f; }
     __syncthreads();
 
-    // Output accumulators: wave w owns dimensions 32 w .. 32 w + 31; element r of lane `lane` is
-    // o[query 32 qb + lane % 32][dimension 32 w + acc_row(r, lane)], in units of P_SCALE.
-    f32x16 o_acc[NQB];
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) o_acc[qb][r] = 0.f;
-
-    // ---- the block's own rows (fp32 keys and values, vector ALU); 16 score columns, absent keys -inf
+    // ---- the block's own rows (fp32 keys and values, vector ALU); absent keys -inf.  The value sum is
+    // held in accumulator layout: wave w owns dimensions 32 w .. 32 w + 31, element r of a lane is
+    // o[query 32 qb + lane % 32][dimension 32 w + acc_row(r, half)], in units of P_SCALE.
     for (int qq = tid >> 4; qq < NQ; qq += 16) {
         const int key = tid & 15;
         float acc = -INFINITY;
@@ -309,8 +293,13 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         S[qq][key] = acc;
     }
     __syncthreads();
-    softmax_tile<NQ, SROW, PROW, false>(S, pp[0], pp[1], run_m, run_l, rescale, 16);
+    softmax_block<NQ>(S, blk_m, blk_l);
     __syncthreads();
+    f32x16 o_blk[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o_blk[qb][r] = 0.f;
     for (int k = 0; k < L; ++k) {
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
@@ -318,111 +307,183 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
                 const float4 v = *reinterpret_cast<const float4 *>(&vb[k][32 * wave + 8 * j + 4 * half]);
-                o_acc[qb][4 * j + 0] += pk * v.x; o_acc[qb][4 * j + 1] += pk * v.y;
-                o_acc[qb][4 * j + 2] += pk * v.z; o_acc[qb][4 * j + 3] += pk * v.w;
+                o_blk[qb][4 * j + 0] += pk * v.x; o_blk[qb][4 * j + 1] += pk * v.y;
+                o_blk[qb][4 * j + 2] += pk * v.z; o_blk[qb][4 * j + 3] += pk * v.w;
             }
         }
     }
-    __syncthreads();
 
-    // ---- prefix tiles
-    const int kblk = wave % KBLK, sqb = wave / KBLK;   // this wave's (key block, query block) of the score phase
-    for (int t0 = 0; t0 < P; t0 += TK) {
+    // ---- this wave's chunks of the prefix: running max / sum per query (both half-waves hold the
+    // same copy) and the value sum for ALL 128 dimensions (4 blocks of 32), in units of P_SCALE
+    float run_m[NQB], run_l[NQB];
+    f32x16 o_acc[NQB][4];
 #pragma unroll
-        for (int n = 0; n < NREQ; ++n) {   // park the tile as fp16 (absent keys: zeros)
-            const int idx = tid + 256 * n, key = idx >> 4, c = idx & 15;
-            *reinterpret_cast<uint4 *>(&kt[key][8 * c]) = bf16x8_to_f16x8(kreg[n]);
-            *reinterpret_cast<uint4 *>(&vt[key][8 * c]) = bf16x8_to_f16x8(vreg[n]);
+    for (int qb = 0; qb < NQB; ++qb) {
+        run_m[qb] = -INFINITY;
+        run_l[qb] = 0.f;
+#pragma unroll
+        for (int db = 0; db < 4; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o_acc[qb][db][r] = 0.f;
+    }
+    for (int c = wave; c < nchunks; c += 4) {
+        uint4 kf[HD / 16];
+#pragma unroll
+        for (int ks = 0; ks < HD / 16; ++ks) kf[ks] = bf16x8_to_f16x8(kreg[ks]);
+        __builtin_amdgcn_wave_barrier();   // (the previous chunk's value reads come before these writes)
+#pragma unroll
+        for (int n = 0; n < CK * HD / 8 / 64; ++n) {
+            const int idx = lane + 64 * n, key = idx >> 4, c16 = idx & 15;
+            *reinterpret_cast<uint4 *>(&vch[wave][key][8 * c16]) = bf16x8_to_f16x8(vreg[n]);
         }
-        __syncthreads();
-        if (t0 + TK < P) request(t0 + TK);
-        {   // scores: 32 keys x 32 queries per wave
-            f32x16 acc;
+        __builtin_amdgcn_wave_barrier();
+        if (c + 4 < nchunks) request(c + 4);
+
+        uint4 p_hi[NQB][2], p_lo[NQB][2];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+        for (int qb = 0; qb < NQB; ++qb) {
+            // scores of the chunk's 32 keys for this lane's query
+            f32x16 sc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sc[r] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < HD / 16; ++ks) {
                 const int col = 16 * ks + 8 * half;
-                const uint4 kf = *reinterpret_cast<const uint4 *>(&kt[32 * kblk + l32][col]);
-                const uint4 q_hi = *reinterpret_cast<const uint4 *>(&qp[0][32 * sqb + l32][col]);
-                const uint4 q_lo = *reinterpret_cast<const uint4 *>(&qp[1][32 * sqb + l32][col]);
-                acc = mma_f16(kf, q_hi, acc);
-                acc = mma_f16(kf, q_lo, acc);
+                const uint4 q_hi = *reinterpret_cast<const uint4 *>(&qp[0][32 * qb + l32][col]);
+                const uint4 q_lo = *reinterpret_cast<const uint4 *>(&qp[1][32 * qb + l32][col]);
+                sc = mma_f16(kf[ks], q_hi, sc);
+                sc = mma_f16(kf[ks], q_lo, sc);
             }
+            float cmax = -INFINITY;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int key = 32 * kblk + acc_row(r, lane);
-                S[32 * sqb + l32][key] = (t0 + key < P) ? acc[r] * (1.0f / Q_SCALE) : -INFINITY;
+                sc[r] = (c * CK + acc_row(r, half) < P) ? sc[r] * (1.0f / Q_SCALE) : -INFINITY;
+                cmax = fmaxf(cmax, sc[r]);
+            }
+            cmax = fmaxf(cmax, __shfl_xor(cmax, 32));   // finite: a chunk holds at least one key
+            const float m_new = fmaxf(run_m[qb], cmax);
+            const float f = (run_m[qb] == -INFINITY) ? 0.f : __expf(run_m[qb] - m_new);
+            float csum = 0.f;
+            uint16_t hi[16], lo[16];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const float pr = __expf(sc[r] - m_new);   // exp(-inf) = 0 for absent keys
+                csum += pr;
+                split2(pr * P_SCALE, hi[r], lo[r]);
+            }
+            csum += __shfl_xor(csum, 32);
+            run_l[qb] = run_l[qb] * f + csum;
+            run_m[qb] = m_new;
+            if (__any(f != 1.0f)) {   // (uniform over the wave: once the maxima have settled nothing is rescaled)
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) o_acc[qb][db][r] *= f;
+            }
+            // the lane's 16 probabilities are its B fragments: k step s holds accumulator rows 8 s .. 8 s + 7
+#pragma unroll
+            for (int s2 = 0; s2 < 2; ++s2) {
+                p_hi[qb][s2] = make_uint4(pack2(hi[8 * s2], hi[8 * s2 + 1]), pack2(hi[8 * s2 + 2], hi[8 * s2 + 3]),
+                                          pack2(hi[8 * s2 + 4], hi[8 * s2 + 5]), pack2(hi[8 * s2 + 6], hi[8 * s2 + 7]));
+                p_lo[qb][s2] = make_uint4(pack2(lo[8 * s2], lo[8 * s2 + 1]), pack2(lo[8 * s2 + 2], lo[8 * s2 + 3]),
+                                          pack2(lo[8 * s2 + 4], lo[8 * s2 + 5]), pack2(lo[8 * s2 + 6], lo[8 * s2 + 7]));
             }
         }
-        __syncthreads();
-        softmax_tile<NQ, SROW, PROW, true>(S, pp[0], pp[1], run_m, run_l, rescale, TK);
-        __syncthreads();
-        {   // values: 32 dimensions x all queries per wave
+        // values: V^T fragments gathered in the same key order (k step s, element e <-> accumulator row 8 s + e)
 #pragma unroll
-            for (int qb = 0; qb < NQB; ++qb) {
-                const float f = rescale[32 * qb + l32];
+        for (int db = 0; db < 4; ++db) {
 #pragma unroll
-                for (int r = 0; r < 16; ++r) o_acc[qb][r] *= f;
-            }
-#pragma unroll
-            for (int ks = 0; ks < TK / 16; ++ks) {
-                // V^T fragment: this lane's dimension, keys 16 ks + 8 half .. + 7
+            for (int s2 = 0; s2 < 2; ++s2) {
                 uint16_t vh[8];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) vh[e] = vt[16 * ks + 8 * half + e][32 * wave + l32];
+                for (int e = 0; e < 8; ++e) vh[e] = vch[wave][acc_row(8 * s2 + e, half)][32 * db + l32];
                 const uint4 vf = make_uint4(pack2(vh[0], vh[1]), pack2(vh[2], vh[3]), pack2(vh[4], vh[5]), pack2(vh[6], vh[7]));
 #pragma unroll
                 for (int qb = 0; qb < NQB; ++qb) {
-                    const uint4 p_hi = *reinterpret_cast<const uint4 *>(&pp[0][32 * qb + l32][16 * ks + 8 * half]);
-                    const uint4 p_lo = *reinterpret_cast<const uint4 *>(&pp[1][32 * qb + l32][16 * ks + 8 * half]);
-                    o_acc[qb] = mma_f16(vf, p_hi, o_acc[qb]);
-                    o_acc[qb] = mma_f16(vf, p_lo, o_acc[qb]);
+                    o_acc[qb][db] = mma_f16(vf, p_hi[qb][s2], o_acc[qb][db]);
+                    o_acc[qb][db] = mma_f16(vf, p_lo[qb][s2], o_acc[qb][db]);
                 }
             }
+        }
+    }
+
+    // ---- merge the five partial results per query in a fixed order: block, waves 0 .. 3
+    if (half == 0) {
+#pragma unroll
+        for (int qb = 0; qb < NQB; ++qb) { w_m[wave][32 * qb + l32] = run_m[qb]; w_l[wave][32 * qb + l32] = run_l[qb]; }
+    }
+    __syncthreads();   // (also: every wave is done with the fp32 queries, whose buffer takes the merged output)
+    float f_blk[NQB], f_own[NQB];
+#pragma unroll
+    for (int qb = 0; qb < NQB; ++qb) {
+        const int q = 32 * qb + l32;
+        float m_tot = blk_m[q];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) m_tot = fmaxf(m_tot, w_m[w][q]);
+        f_blk[qb] = __expf(blk_m[q] - m_tot);
+        float l_tot = blk_l[q] * f_blk[qb];
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float fw = (w_m[w][q] == -INFINITY) ? 0.f : __expf(w_m[w][q] - m_tot);
+            l_tot += w_l[w][q] * fw;
+            if (w == wave) f_own[qb] = fw;
+        }
+        if (wave == 0 && half == 0) tot_l[q] = l_tot;
+#pragma unroll
+        for (int j = 0; j < 4; ++j)   // the block's partial: this wave's 32 dimensions
+            *reinterpret_cast<float4 *>(&qs[q][32 * wave + 8 * j + 4 * half]) =
+                make_float4(o_blk[qb][4 * j] * f_blk[qb], o_blk[qb][4 * j + 1] * f_blk[qb],
+                            o_blk[qb][4 * j + 2] * f_blk[qb], o_blk[qb][4 * j + 3] * f_blk[qb]);
+    }
+    __syncthreads();
+    for (int w = 0; w < 4; ++w) {
+        if (wave == w && w < nchunks) {   // (uniform over the wave)
+#pragma unroll
+            for (int qb = 0; qb < NQB; ++qb)
+#pragma unroll
+                for (int db = 0; db < 4; ++db)
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        float4 *dst = reinterpret_cast<float4 *>(&qs[32 * qb + l32][32 * db + 8 * j + 4 * half]);
+                        float4 v = *dst;
+                        v.x += o_acc[qb][db][4 * j] * f_own[qb]; v.y += o_acc[qb][db][4 * j + 1] * f_own[qb];
+                        v.z += o_acc[qb][db][4 * j + 2] * f_own[qb]; v.w += o_acc[qb][db][4 * j + 3] * f_own[qb];
+                        *dst = v;
+                    }
         }
         __syncthreads();
     }
 
-    // ---- normalise, stage as [query][dimension] (the fp32 query buffer is free by now), write the planes
-#pragma unroll
-    for (int qb = 0; qb < NQB; ++qb) {
-        const float inv = 1.0f / (run_l[32 * qb + l32] * P_SCALE);
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            *reinterpret_cast<float4 *>(&qs[32 * qb + l32][32 * wave + 8 * j + 4 * half]) =
-                make_float4(o_acc[qb][4 * j] * inv, o_acc[qb][4 * j + 1] * inv, o_acc[qb][4 * j + 2] * inv,
-                            o_acc[qb][4 * j + 3] * inv);
-    }
-    __syncthreads();
+    // ---- normalise and write the activation planes
     for (int idx = tid; idx < Q * (HD / 8); idx += 256) {
         const int qq = idx / (HD / 8), c = idx % (HD / 8);
         const int hrep = qq / L, i = qq % L, row = b * L + i;
+        const float inv = 1.0f / (tot_l[qq] * P_SCALE);
         float x[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] = qs[qq][8 * c + e];
+        for (int e = 0; e < 8; ++e) x[e] = qs[qq][8 * c + e] * inv;
         split_store(x, a.o_planes, act_chunk_index(row, (g * rep + hrep) * (HD / 8) + c, a.nIb), a.plane_stride);
     }
 }
 
-template <int NQB, int TK>
+template <int NQB>
 hipError_t attn_configure_one() {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<NQB, TK>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)AttnLds<32 * NQB, TK>::total);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<NQB>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)AttnLds<32 * NQB>::total);
 }
 
-template <int NQB, int TK>
+template <int NQB>
 hipError_t attn_launch_one(const AttnArgs &a, int B, hipStream_t st) {
-    constexpr size_t lds = AttnLds<32 * NQB, TK>::total;
-    hipLaunchKernelGGL((attn_kernel<NQB, TK>), dim3(a.nkv, B), dim3(256), lds, st, a);
+    constexpr size_t lds = AttnLds<32 * NQB>::total;
+    hipLaunchKernelGGL((attn_kernel<NQB>), dim3(a.nkv, B), dim3(256), lds, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t tbody_configure() {
-    hipError_t e = attn_configure_one<1, 128>();
-    if (e == hipSuccess) e = attn_configure_one<2, 64>();
+    hipError_t e = attn_configure_one<1>();
+    if (e == hipSuccess) e = attn_configure_one<2>();
     return e;
 }
 
@@ -466,8 +527,8 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
     a.P_max = P_max; a.nh = nh; a.nkv = nkv; a.L = L;
     a.o_planes = o_planes; a.plane_stride = plane_stride; a.nIb = nIb;
     const int Q = (nh / nkv) * L;
-    if (Q <= 32) return attn_launch_one<1, 128>(a, B, st);
-    return attn_launch_one<2, 64>(a, B, st);
+    if (Q <= 32) return attn_launch_one<1>(a, B, st);
+    return attn_launch_one<2>(a, B, st);
 }
 
 }  // namespace mrp
