@@ -325,7 +325,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {"workload": f"config {cfg.cid} ({cfg.name}): d={d} V={V} B={B} block={L} rows={M} K={K} "
                                f"tau={cfg.tau}" + (f" tau_remask={cfg.tau_remask}" if cfg.tau_remask >= 0 else ""),
-                   "accumulate": "fp32", "logit_state": "fp32"},
+                   "accumulate": "fp32", "logit_state": "fp32", "lm_head_operands": "bf16",
+                   "head_body_operands": "fp32 activations as two fp16 terms, bf16 weights converted to fp16"},
         "roofline": roof,
         "cpu_baseline": cpu,
     }
