@@ -161,24 +161,24 @@ __device__ __forceinline__ f32x16 mma_f16(const uint4 &x, const uint4 &y, const 
 __device__ __forceinline__ int acc_row(int r, int half) { return 8 * (r >> 2) + 4 * half + (r & 3); }
 
 // LDS carve-up of the attention kernel (NQ query slots); offsets in bytes
-template <int NQ>
+template <int NQ, int NW>
 struct AttnLds {
     static constexpr size_t qs = 0;                                                // float [NQ][HD] (later: merged output)
     static constexpr size_t kb = qs + sizeof(float) * NQ * HD;                     // float [LB][HD]
     static constexpr size_t vb = kb + sizeof(float) * LB * HD;                     // float [LB][HD]
     static constexpr size_t S = vb + sizeof(float) * LB * HD;                      // float [NQ][SCOLS]
     static constexpr size_t stat = S + sizeof(float) * NQ * SCOLS;                 // float [3][NQ] block max / sum / scratch
-    static constexpr size_t wstat = stat + sizeof(float) * 3 * NQ;                 // float [2][4][NQ] per-wave max / sum
-    static constexpr size_t qp = wstat + sizeof(float) * 8 * NQ;                   // half [2][NQ][KROW]
-    static constexpr size_t vch = qp + sizeof(uint16_t) * 2 * NQ * KROW;           // half [4][CK][KROW] per-wave value chunk
-    static constexpr size_t total = vch + sizeof(uint16_t) * 4 * CK * KROW;
+    static constexpr size_t wstat = stat + sizeof(float) * 3 * NQ;                 // float [2][NW][NQ] per-wave max / sum
+    static constexpr size_t qp = wstat + sizeof(float) * 2 * NW * NQ;              // half [2][NQ][KROW]
+    static constexpr size_t vch = qp + sizeof(uint16_t) * 2 * NQ * KROW;           // half [NW][CK][HD] per-wave value chunk
+    static constexpr size_t total = vch + sizeof(uint16_t) * NW * CK * HD;
 };
 
 // softmax of the block phase: S[qq][0 .. 16) holds raw scores (-inf = no key) and is replaced by
 // exp(score - max); 256 / NQ adjacent lanes share a query.
-template <int NQ>
+template <int NQ, int NT>
 __device__ __forceinline__ void softmax_block(float (*S)[SCOLS], float *blk_m, float *blk_l) {
-    constexpr int TPQ = 256 / NQ;   // 4 or 8 lanes per query, inside one wave
+    constexpr int TPQ = NT / NQ;    // 4 .. 16 lanes per query, inside one wave
     const int qq = threadIdx.x / TPQ, part = threadIdx.x % TPQ;
     float mx = -INFINITY;
     for (int c = part; c < 16; c += TPQ) mx = fmaxf(mx, S[qq][c]);
@@ -195,11 +195,13 @@ __device__ __forceinline__ void softmax_block(float (*S)[SCOLS], float *blk_m, f
     if (part == 0) { blk_m[qq] = mx; blk_l[qq] = sum; }
 }
 
-// NQB: blocks of 32 query slots (1 or 2)
-template <int NQB>
-__global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
-    constexpr int NQ = 32 * NQB;
-    using Lds = AttnLds<NQ>;
+// NQB: blocks of 32 query slots (1 or 2); NW: wavefronts (8 = two per SIMD, with the next chunk's
+// requests left to the other wave to hide; 4 = one per SIMD, each requesting one chunk ahead)
+template <int NQB, int NW>
+__global__ __launch_bounds__(64 * NW) void attn_kernel(AttnArgs a) {
+    constexpr int NQ = 32 * NQB, NT = 64 * NW;
+    constexpr bool AHEAD = NW == 4;
+    using Lds = AttnLds<NQ, NW>;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem_raw[];
     float (*qs)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::qs);       // rotated, scaled queries (fp32)
     float (*kb)[HD] = reinterpret_cast<float (*)[HD]>(smem_raw + Lds::kb);       // rotated block keys
@@ -208,10 +210,10 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     float *blk_m = reinterpret_cast<float *>(smem_raw + Lds::stat);
     float *blk_l = blk_m + NQ;
     float *tot_l = blk_l + NQ;
-    float (*w_m)[NQ] = reinterpret_cast<float (*)[NQ]>(smem_raw + Lds::wstat);    // [4] per-wave running max
-    float (*w_l)[NQ] = w_m + 4;                                                   // [4] per-wave running sum
+    float (*w_m)[NQ] = reinterpret_cast<float (*)[NQ]>(smem_raw + Lds::wstat);    // [NW] per-wave running max
+    float (*w_l)[NQ] = w_m + NW;                                                  // [NW] per-wave running sum
     uint16_t (*qp)[NQ][KROW] = reinterpret_cast<uint16_t (*)[NQ][KROW]>(smem_raw + Lds::qp);   // [2] query planes
-    uint16_t (*vch)[CK][KROW] = reinterpret_cast<uint16_t (*)[CK][KROW]>(smem_raw + Lds::vch); // [4] value chunks
+    uint16_t (*vch)[CK][HD] = reinterpret_cast<uint16_t (*)[CK][HD]>(smem_raw + Lds::vch);     // [NW] value chunks
 
     const int g = blockIdx.x, b = blockIdx.y, tid = threadIdx.x;
     const int lane = tid & 63, wave = tid >> 6, l32 = lane & 31, half = lane >> 5;
@@ -244,10 +246,10 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
                 vreg[n] = *reinterpret_cast<const uint4 *>(a.vc + (((size_t)b * a.P_max + tv) * a.nkv + g) * HD + 8 * c16);
         }
     };
-    if (wave < nchunks) request(wave);
+    if (AHEAD && wave < nchunks) request(wave);
 
     // ---- prologue: the block's q (rotated, scaled; fp32 and as two fp16 planes), k (rotated) and v
-    for (int idx = tid; idx < NQ * (HD / 2); idx += 256) {
+    for (int idx = tid; idx < NQ * (HD / 2); idx += NT) {
         const int qq = idx / (HD / 2), j = idx % (HD / 2);
         float r0 = 0.f, r1 = 0.f;
         if (qq < Q) {
@@ -266,7 +268,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         split2(r1 * Q_SCALE, hi, lo);
         qp[0][qq][j + HD / 2] = hi; qp[1][qq][j + HD / 2] = lo;
     }
-    for (int idx = tid; idx < L * (HD / 2); idx += 256) {
+    for (int idx = tid; idx < L * (HD / 2); idx += NT) {
         const int i = idx / (HD / 2), j = idx % (HD / 2), row = b * L + i;
         const size_t off = (size_t)row * a.ldq + qd + (size_t)g * HD;
         const float x0 = sum_col(a, off + j), x1 = sum_col(a, off + j + HD / 2);
@@ -274,7 +276,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         kb[i][j] = x0 * cs.x - x1 * cs.y;
         kb[i][j + HD / 2] = x1 * cs.x + x0 * cs.y;
     }
-    for (int idx = tid; idx < L * HD; idx += 256) {
+    for (int idx = tid; idx < L * HD; idx += NT) {
         const int i = idx / HD, e = idx % HD, row = b * L + i;
         vb[i][e] = sum_col(a, (size_t)row * a.ldq + qd + kvd + (size_t)g * HD + e);
     }
@@ -283,7 +285,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     // ---- the block's own rows (fp32 keys and values, vector ALU); absent keys -inf.  The value sum is
     // held in accumulator layout: wave w owns dimensions 32 w .. 32 w + 31, element r of a lane is
     // o[query 32 qb + lane % 32][dimension 32 w + acc_row(r, half)], in units of P_SCALE.
-    for (int qq = tid >> 4; qq < NQ; qq += 16) {
+    for (int qq = tid >> 4; qq < NQ; qq += NT / 16) {
         const int key = tid & 15;
         float acc = -INFINITY;
         if (key < L) {
@@ -293,14 +295,14 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         S[qq][key] = acc;
     }
     __syncthreads();
-    softmax_block<NQ>(S, blk_m, blk_l);
+    softmax_block<NQ, NT>(S, blk_m, blk_l);
     __syncthreads();
     f32x16 o_blk[NQB];
 #pragma unroll
     for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
         for (int r = 0; r < 16; ++r) o_blk[qb][r] = 0.f;
-    for (int k = 0; k < L; ++k) {
+    for (int k = 0; k < L && wave < 4; ++k) {   // (waves 0 .. 3 own the 4 x 32 dimensions of the block's partial)
 #pragma unroll
         for (int qb = 0; qb < NQB; ++qb) {
             const float pk = S[32 * qb + l32][k] * P_SCALE;
@@ -326,7 +328,8 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) o_acc[qb][db][r] = 0.f;
     }
-    for (int c = wave; c < nchunks; c += 4) {
+    for (int c = wave; c < nchunks; c += NW) {
+        if (!AHEAD) request(c);
         uint4 kf[HD / 16];
 #pragma unroll
         for (int ks = 0; ks < HD / 16; ++ks) kf[ks] = bf16x8_to_f16x8(kreg[ks]);
@@ -337,7 +340,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
             *reinterpret_cast<uint4 *>(&vch[wave][key][8 * c16]) = bf16x8_to_f16x8(vreg[n]);
         }
         __builtin_amdgcn_wave_barrier();
-        if (c + 4 < nchunks) request(c + 4);
+        if (AHEAD && c + NW < nchunks) request(c + NW);
 
         uint4 p_hi[NQB][2], p_lo[NQB][2];
 #pragma unroll
@@ -419,25 +422,27 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
         const int q = 32 * qb + l32;
         float m_tot = blk_m[q];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) m_tot = fmaxf(m_tot, w_m[w][q]);
+        for (int w = 0; w < NW; ++w) m_tot = fmaxf(m_tot, w_m[w][q]);
         f_blk[qb] = __expf(blk_m[q] - m_tot);
         float l_tot = blk_l[q] * f_blk[qb];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const float fw = (w_m[w][q] == -INFINITY) ? 0.f : __expf(w_m[w][q] - m_tot);
             l_tot += w_l[w][q] * fw;
             if (w == wave) f_own[qb] = fw;
         }
         if (wave == 0 && half == 0) tot_l[q] = l_tot;
+        if (wave < 4) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)   // the block's partial: this wave's 32 dimensions
-            *reinterpret_cast<float4 *>(&qs[q][32 * wave + 8 * j + 4 * half]) =
-                make_float4(o_blk[qb][4 * j] * f_blk[qb], o_blk[qb][4 * j + 1] * f_blk[qb],
-                            o_blk[qb][4 * j + 2] * f_blk[qb], o_blk[qb][4 * j + 3] * f_blk[qb]);
+            for (int j = 0; j < 4; ++j)   // the block's partial: this wave's 32 dimensions
+                *reinterpret_cast<float4 *>(&qs[q][32 * wave + 8 * j + 4 * half]) =
+                    make_float4(o_blk[qb][4 * j] * f_blk[qb], o_blk[qb][4 * j + 1] * f_blk[qb],
+                                o_blk[qb][4 * j + 2] * f_blk[qb], o_blk[qb][4 * j + 3] * f_blk[qb]);
+        }
     }
     __syncthreads();
-    for (int w = 0; w < 4; ++w) {
-        if (wave == w && w < nchunks) {   // (uniform over the wave)
+    for (int w = 0; w < NW && w < nchunks; ++w) {   // (uniform over the workgroup)
+        if (wave == w) {
 #pragma unroll
             for (int qb = 0; qb < NQB; ++qb)
 #pragma unroll
@@ -455,7 +460,7 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     }
 
     // ---- normalise and write the activation planes
-    for (int idx = tid; idx < Q * (HD / 8); idx += 256) {
+    for (int idx = tid; idx < Q * (HD / 8); idx += NT) {
         const int qq = idx / (HD / 8), c = idx % (HD / 8);
         const int hrep = qq / L, i = qq % L, row = b * L + i;
         const float inv = 1.0f / (tot_l[qq] * P_SCALE);
@@ -466,24 +471,24 @@ __global__ __launch_bounds__(256) void attn_kernel(AttnArgs a) {
     }
 }
 
-template <int NQB>
+template <int NQB, int NW>
 hipError_t attn_configure_one() {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<NQB>),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)AttnLds<32 * NQB>::total);
+    return hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_kernel<NQB, NW>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)AttnLds<32 * NQB, NW>::total);
 }
 
-template <int NQB>
+template <int NQB, int NW>
 hipError_t attn_launch_one(const AttnArgs &a, int B, hipStream_t st) {
-    constexpr size_t lds = AttnLds<32 * NQB>::total;
-    hipLaunchKernelGGL((attn_kernel<NQB>), dim3(a.nkv, B), dim3(256), lds, st, a);
+    constexpr size_t lds = AttnLds<32 * NQB, NW>::total;
+    hipLaunchKernelGGL((attn_kernel<NQB, NW>), dim3(a.nkv, B), dim3(64 * NW), lds, st, a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t tbody_configure() {
-    hipError_t e = attn_configure_one<1>();
-    if (e == hipSuccess) e = attn_configure_one<2>();
+    hipError_t e = attn_configure_one<1, 8>();
+    if (e == hipSuccess) e = attn_configure_one<2, 4>();
     return e;
 }
 
@@ -527,8 +532,8 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
     a.P_max = P_max; a.nh = nh; a.nkv = nkv; a.L = L;
     a.o_planes = o_planes; a.plane_stride = plane_stride; a.nIb = nIb;
     const int Q = (nh / nkv) * L;
-    if (Q <= 32) return attn_launch_one<1>(a, B, st);
-    return attn_launch_one<2>(a, B, st);
+    if (Q <= 32) return attn_launch_one<1, 8>(a, B, st);
+    return attn_launch_one<2, 4>(a, B, st);
 }
 
 }  // namespace mrp
