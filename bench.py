@@ -32,10 +32,11 @@ HBM_PEAK_GBS = 8000.0        # MI355X published HBM3E bandwidth
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X published dense bf16
 
 
-def traffic_from_profile(cid: int):
-    """HBM bytes per LM-head launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-    as recorded in the committed counter summary; None if no summary exists."""
-    path = os.path.join(ROOT, "profiles", f"lm_head_cfg{cid}_pmc.txt")
+def traffic_from_profile(cid, name: str = ""):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), as recorded in the
+    committed counter summary (the LM-head kernel of configuration `cid`, or the summary `name`);
+    None if no summary exists."""
+    path = os.path.join(ROOT, "profiles", name or f"lm_head_cfg{cid}_pmc.txt")
     try:
         with open(path) as f:
             m = re.search(r"^TRAFFIC_BYTES_PER_LAUNCH\s*=\s*([0-9.eE+]+)", f.read(), re.M)
@@ -85,7 +86,8 @@ def bench_kl_loss(args, np, torch, mi, mrp) -> dict:
     byt += 4.0 * M * V * (1 - mask.mean())
     ach = byt / (ev / args.steps) / 1e9
     roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
-            "traffic": None, "kernel": "kl_partial_kernel + kl_finish_kernel + kl_grad_kernel",
+            "traffic": traffic_from_profile(None, "kl_loss_pmc.txt") if (M, V) == (1024, 151936) else None,
+            "kernel": "kl_partial_kernel + kl_finish_kernel + kl_grad_kernel",
             "kernel_ms": 1e3 * ev / args.steps}
     cpu = None
     if not args.skip_cpu_baseline:
@@ -114,7 +116,8 @@ def bench_residual_rms(args, np, torch, mi, mrp) -> dict:
     flop = (136 + 2 * 153) * float(nb) * N       # per entry: 136 fp64 subtractions, 153 fused multiply-adds
     ach = flop / (ev / args.steps) / 1e12
     roof = {"bound": "alu", "achieved": ach, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": ach / FP64_VECTOR_PEAK_TFLOPS, "traffic": None, "kernel": "rms_partial_kernel<17>",
+            "frac": ach / FP64_VECTOR_PEAK_TFLOPS, "traffic": traffic_from_profile(None, "residual_rms_pmc.txt"),
+            "kernel": "rms_partial_kernel<17>",
             "kernel_ms": 1e3 * ev / args.steps, "hbm_GBps": 4.0 * nb * S * N / (ev / args.steps) / 1e9}
     cpu = None
     if not args.skip_cpu_baseline:
