@@ -84,6 +84,24 @@ def test_scalar_vocab_path_and_max_accept():
     prob.close()
 
 
+@pytest.mark.timeout(600)
+def test_maximum_hidden_size_and_block_length():
+    """The largest hidden size (d = 8192) and block length (L = 64) the library accepts."""
+    cfg = mi.straddling(mi.config(0, d=8192, V=1024, B=2, L=64, K=1))
+    prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=0.9, tau_remask=0.5, max_accept=1))
+    prob.close()
+
+
+def test_block_of_one_position():
+    """L = 1: every sequence is a single row; the forced reveal takes it at state 0, later states have
+    nothing left to reveal (draft (-1, -1)) and keep the conditioning token."""
+    cfg = mi.straddling(mi.config(0, B=9, L=1, K=2))
+    prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=0.9))
+    prob.close()
+    assert np.all(g.draft_pos[:, 0] == 0) and np.all(g.draft_pos[:, 1:] == -1)
+    assert np.all(g.masked == 0)
+
+
 def test_many_rows_wide_tile_static_top2():
     # M = 336 > 128 selects the 256-row activation tile (two row groups, the second ragged)
     cfg = mi.straddling(mi.config(0, d=256, V=2048 + 64, B=21, L=16))
