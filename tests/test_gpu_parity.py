@@ -102,6 +102,15 @@ def test_block_of_one_position():
     assert np.all(g.masked == 0)
 
 
+@pytest.mark.parametrize("B,L", [(12, 64), (40, 7), (112, 7)])
+def test_tile_major_partials_with_odd_and_long_blocks(B, L):
+    """The GEMM kernels that own whole row tiles write their vocabulary partials tile-major; the merge
+    then runs threads over a sequence's rows (block lengths that are not a power of two, and the longest)."""
+    cfg = mi.straddling(mi.config(0, d=256, V=4096 + 36, B=B, L=L, K=1))
+    prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=0.9, tau_remask=0.5), seqs=list(range(0, B, max(1, B // 6))))
+    prob.close()
+
+
 def test_many_rows_wide_tile_static_top2():
     # M = 336 > 128 selects the 256-row activation tile (two row groups, the second ragged)
     cfg = mi.straddling(mi.config(0, d=256, V=2048 + 64, B=21, L=16))
