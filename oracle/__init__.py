@@ -31,7 +31,7 @@ class _Cfg(C.Structure):
                 ("rms_eps", C.c_double), ("tau", C.c_double), ("r_min", C.c_int),
                 ("max_accept", C.c_int), ("carry_hidden", C.c_int), ("tau_remask", C.c_double),
                 ("head_reveal", C.c_int), ("fresh_block", C.c_int), ("state_offset", C.c_int),
-                ("run_state0", C.c_int), ("remask_mode", C.c_int)]
+                ("run_state0", C.c_int), ("remask_mode", C.c_int), ("round_y", C.c_int)]
 
 
 _lib = None
@@ -61,9 +61,11 @@ def _chk(a, dtype, shape=None):
 
 def make_cfg(d, V, B, L, K, tau=0.9, r_min=1, max_accept=0, carry_hidden=1, tau_remask=-1.0,
              head_reveal=1, fresh_block=1, state_offset=0, run_state0=1, rms_eps=1e-6,
-             remask_mode=0) -> _Cfg:
+             remask_mode=0, round_y=0) -> _Cfg:
+    """round_y=0: the plain definition (no intermediate rounded); round_y=1: the LM-head operand y
+    is rounded to bf16 (used to compare decisions with a bf16-operand implementation bit for bit)."""
     return _Cfg(d, V, B, L, K, rms_eps, tau, r_min, max_accept, carry_hidden, tau_remask,
-                head_reveal, fresh_block, state_offset, run_state0, remask_mode)
+                head_reveal, fresh_block, state_offset, run_state0, remask_mode, round_y)
 
 
 def bf16_round(x: np.ndarray) -> np.ndarray:
@@ -149,6 +151,18 @@ def verify_accept_joint(verify, draft_pos, draft_tok):
     lib().orc_verify_accept_joint(B, L, V, K, _p(verify), _p(draft_pos), _p(draft_tok), _p(match), _p(alen),
                                   _p(corr))
     return match, alen, corr
+
+
+def build_candidates(x_t, masked_t, draft_pos, draft_tok, mask_token: int):
+    """Candidate blocks of the joint verification.  x_t int32 [B][L], masked_t uint8 [B][L], drafts int32
+    [B][K]; returns (cand_tok int32 [B][K+1][L], cand_masked uint8 [B][K+1][L])."""
+    B, L = x_t.shape
+    K = draft_pos.shape[1]
+    _chk(x_t, np.int32); _chk(masked_t, np.uint8, (B, L)); _chk(draft_pos, np.int32, (B, K)); _chk(draft_tok, np.int32, (B, K))
+    ct = np.empty((B, K + 1, L), np.int32); cm = np.empty((B, K + 1, L), np.uint8)
+    lib().orc_build_candidates(B, L, K, _p(x_t), _p(masked_t), _p(draft_pos), _p(draft_tok), C.c_int32(mask_token),
+                               _p(ct), _p(cm))
+    return ct, cm
 
 
 def kl_loss(teacher, student, row_mask=None, scale=1.0, want_grad=True):
@@ -274,7 +288,7 @@ class ChainOut:
     draft_pos: np.ndarray    # [B][K+1]
     draft_tok: np.ndarray
     remasked: np.ndarray     # [(K+1)][M]
-    y: Optional[np.ndarray]  # [K][M][d] bf16-rounded LM-head operand
+    y: Optional[np.ndarray]  # [K][M][d] LM-head operand (bf16-rounded when cfg.round_y)
     gap: np.ndarray          # [(K+1)][M] top-2 logit gap of every state
     x_tok: Optional[np.ndarray] = None   # [M] token recorded when a position was revealed (-1: none)
 

@@ -31,6 +31,8 @@
  *   - joint verification: the K + 1 candidates C^0..C^K (candidate k holds the
  *       first k drafts) are scored in one backbone pass; draft j is checked
  *       against candidate j (Figure 1 (d)).
+ *   - candidate blocks: candidate k is the block with the first k drafts written
+ *       in and every other position as before the drafting (Figure 1 (d)).
  *   - verify: a draft is accepted where the verifier's argmax equals the
  *       drafted token (Algorithm 3); the accepted length is the longest
  *       all-matching prefix of the draft list.
@@ -47,9 +49,15 @@
  *
  * The default head body is the benchmark's lightweight layout (not the paper's
  * transformer layers): x = [h ; E[cond_tok]], a = W1 x, s = SiLU(a),
- * u = W2 s, Delta = u, y = bf16(RMSNorm(u) * gamma), delta = W_lm y.
- * The only rounding of an intermediate is y -> bf16: the LM-head projection
- * is defined on a bf16 activation operand.  Everything else is fp64.
+ * u = W2 s, Delta = u, y = RMSNorm(u) * gamma, delta = W_lm y, all in fp64:
+ * with round_y = 0 no intermediate is rounded -- this is the plain definition
+ * l <- l + W_lm (RMSNorm(u) gamma) (Section 3.2, Algorithm 2), and the logit
+ * tolerance of the parity rule is stated against it.  round_y = 1 rounds y --
+ * and only y -- to bf16 before the LM-head projection: the arithmetic of an
+ * implementation whose LM-head activation operand is bf16.  It is used to
+ * compare discrete decisions bit for bit (both sides then take each decision
+ * on logits that differ by fp32 round-off only); it is a variant, not the
+ * definition.
  *
  * Ties: lowest vocabulary index wins an argmax; lowest position wins a
  * confidence tie.  Reveal compares strictly (conf > tau), remask compares
@@ -59,7 +67,9 @@
  * closed forms (uniform row, one-hot-plus-a row), shift invariance,
  * permutation equivariance, sum of probabilities, zero-residual invariance,
  * the softmax half-Lipschitz bound, tau = 0 / tau >= 1 reveal sets, the cap
- * values, brute-force longest matching prefix, remask set inclusions;
+ * values, brute-force longest matching prefix, remask set inclusions; a chain
+ * resumed head by head against the full run; the candidate blocks against a
+ * by-hand example and their nesting invariants;
  * KL against scipy's softmax / rel_entr, a two-class closed form, finite
  * differences and the one-hot cross-entropy limit; residual magnitudes against
  * a hand-worked example, a linear ramp and numpy's norm; the transformer layer
@@ -92,6 +102,7 @@ typedef struct {
     int run_state0;      /* 1: reduce z and reveal (state 0) before the heads */
     int remask_mode;     /* 0: remask on the row's top-1 probability; 1: on the probability the updated
                             logits give to the token that was revealed there */
+    int round_y;         /* 0: y stays fp64 (the definition); 1: y is rounded to bf16 before W_lm y */
 } orc_cfg;
 
 /* threads the parallel loops will use */
@@ -152,8 +163,8 @@ void orc_reduce_rows(const double *z, int M, int V, int32_t *tok, double *conf, 
 
 /* Head body for every row i of every sequence b = i / L.
  *   hrun [M][d] in/out (updated only if carry_hidden)
- *   u_out, y_out [M][d] (may be NULL): pre-norm output and bf16-rounded
- *   normalised output. */
+ *   u_out, y_out [M][d] (may be NULL): pre-norm output and normalised output
+ *   (rounded to bf16 when round_y is set). */
 void orc_head_mlp(const orc_cfg *c, const uint16_t *W1, const uint16_t *W2, const uint16_t *gamma,
                   const uint16_t *E, const int32_t *cond_tok, double *hrun, double *u_out,
                   double *y_out) {
@@ -185,7 +196,8 @@ void orc_head_mlp(const orc_cfg *c, const uint16_t *W1, const uint16_t *W2, cons
             }
             const double inv = 1.0 / sqrt(ss / d + c->rms_eps);
             for (int j = 0; j < d; ++j) {
-                const double y = orc_bf16_round(u[j] * inv * bf16_bits_to_double(gamma[j]));
+                const double yd = u[j] * inv * bf16_bits_to_double(gamma[j]);
+                const double y = c->round_y ? orc_bf16_round(yd) : yd;
                 if (y_out) y_out[(size_t)i * d + j] = y;
                 if (u_out) u_out[(size_t)i * d + j] = u[j];
                 if (c->carry_hidden) hrun[(size_t)i * d + j] += u[j];
@@ -310,7 +322,7 @@ void orc_tlayer(const orc_tcfg *t, int d, int L, double eps, const uint16_t *Wqk
 }
 
 /* Transformer head body for every sequence: u0 = Wf [hrun ; e], D layers, then as the MLP body:
- * y = bf16(RMSNorm(u_D) gamma), hrun += u_D if carry_hidden.  The per-layer arrays have D entries. */
+ * y = RMSNorm(u_D) gamma (rounded to bf16 when round_y is set), hrun += u_D if carry_hidden.  The per-layer arrays have D entries. */
 void orc_head_transformer(const orc_cfg *c, const orc_tcfg *t, const uint16_t *Wf,
                           const uint16_t *const *Wqkv, const uint16_t *const *Wo, const uint16_t *const *Wgu,
                           const uint16_t *const *Wdown, const uint16_t *const *g1, const uint16_t *const *g2,
@@ -337,7 +349,7 @@ void orc_head_transformer(const orc_cfg *c, const orc_tcfg *t, const uint16_t *W
             const size_t row = (size_t)b * L + i;
             rmsnorm_gain(U + (size_t)i * d, gamma, d, c->rms_eps, yn);
             for (int j = 0; j < d; ++j) {
-                if (y_out) y_out[row * d + j] = orc_bf16_round(yn[j]);
+                if (y_out) y_out[row * d + j] = c->round_y ? orc_bf16_round(yn[j]) : yn[j];
                 if (u_out) u_out[row * d + j] = U[(size_t)i * d + j];
                 if (c->carry_hidden) hrun[row * d + j] += U[(size_t)i * d + j];
             }
@@ -515,6 +527,32 @@ void orc_verify_accept_joint(int B, int L, int V, int K, const float *verify, co
         }
         accept_len[b] = alen;
     }
+}
+
+/* Candidate blocks of the joint verification (Figure 1 (d)): from the block x_t (tokens of its L
+ * positions, masked_t = 1 where a position still holds the mask token) and the K drafts of a
+ * chain step, in draft order, build the K + 1 candidates C^0 .. C^K: candidate k is x_t with the
+ * first k drafts written in, everything else as in x_t.  cand_tok / cand_masked are
+ * [B][K+1][L]; a masked position holds mask_token.  A missing draft (pos < 0) adds nothing, so the
+ * candidates from it on repeat the one before. */
+void orc_build_candidates(int B, int L, int K, const int32_t *x_t, const uint8_t *masked_t,
+                          const int32_t *draft_pos, const int32_t *draft_tok, int32_t mask_token,
+                          int32_t *cand_tok, uint8_t *cand_masked) {
+    for (int b = 0; b < B; ++b)
+        for (int k = 0; k <= K; ++k) {
+            int32_t *ct = cand_tok + ((size_t)b * (K + 1) + k) * L;
+            uint8_t *cm = cand_masked + ((size_t)b * (K + 1) + k) * L;
+            for (int p = 0; p < L; ++p) {
+                cm[p] = masked_t[(size_t)b * L + p] ? 1 : 0;
+                ct[p] = cm[p] ? mask_token : x_t[(size_t)b * L + p];
+            }
+            for (int j = 0; j < k; ++j) {
+                const int pos = draft_pos[(size_t)b * K + j];
+                if (pos < 0 || pos >= L) continue;
+                ct[pos] = draft_tok[(size_t)b * K + j];
+                cm[pos] = 0;
+            }
+        }
 }
 
 /* Training objective of a head (Section 3.3, Equation 3), written as its definition: for each

@@ -113,10 +113,18 @@ def test_head_mlp_matches_library_matmul(d, V, B, L):
     u, y = orc.head_mlp(cfg, W1, W2, g, E, cond, hrun)
     u_ref, y_ref = _numpy_head(W1, W2, g, E, cond, h0, L)
     np.testing.assert_allclose(u, u_ref, rtol=1e-11, atol=1e-12)
-    # y is the bf16 rounding of the normalised output: within half a bf16 step of it,
-    # and exactly representable in bf16
-    assert np.all(np.abs(y - y_ref) <= np.abs(y_ref) * 2.0 ** -8 + 1e-30)
-    np.testing.assert_array_equal(y, val(bits(y)))
+    # the definition: no intermediate is rounded
+    np.testing.assert_allclose(y, y_ref, rtol=1e-11, atol=1e-12)
+    # the bf16-operand variant: y is the bf16 rounding of the normalised output (within half a
+    # bf16 step of it, exactly representable in bf16); nothing upstream of it changes
+    cfg_r = orc.make_cfg(d, V, B, L, 1, round_y=1)
+    h_r = h0.copy()
+    u_r, y_r = orc.head_mlp(cfg_r, W1, W2, g, E, cond, h_r)
+    np.testing.assert_array_equal(u_r, u)
+    np.testing.assert_array_equal(h_r, hrun)
+    assert np.all(np.abs(y_r - y_ref) <= np.abs(y_ref) * 2.0 ** -8 + 1e-30)
+    np.testing.assert_array_equal(y_r, val(bits(y_r)))
+    assert np.mean(y_r == val(bits(y))) > 0.999            # (a rounding tie may flip under 1e-12 noise)
     np.testing.assert_allclose(hrun, h0 + u_ref, rtol=1e-11, atol=1e-12)      # h <- h + Delta
     cfg2 = orc.make_cfg(d, V, B, L, 1, carry_hidden=0)
     h1 = h0.copy()
@@ -194,8 +202,17 @@ def test_zero_residual_leaves_logits_unchanged():
 def test_chain_matches_library_composition_config0():
     """Whole chain on the tiny configuration against a numpy restatement built from
     library matmul / logsumexp (control flow: greedy forced reveal only)."""
+    _chain_against_library(round_y=0)
+
+
+def test_chain_matches_library_composition_config0_bf16_operand():
+    """The same with the LM-head operand rounded to bf16 (the variant decisions are compared against)."""
+    _chain_against_library(round_y=1)
+
+
+def _chain_against_library(round_y):
     cfg, W, E, heads, h, z0 = _tiny_problem()
-    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, tau=cfg.tau)
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, tau=cfg.tau, round_y=round_y)
     out = orc.chain_step(oc, E, W, heads, z0, val(h), dump_y=True)
     z = z0.astype(np.float64); hrun = val(h)
     masked = np.ones(cfg.M, bool)
@@ -203,13 +220,17 @@ def test_chain_matches_library_composition_config0():
         if k > 0:
             u, y = _numpy_head(*heads[k - 1], E, cond, hrun, cfg.L)
             hrun = hrun + u
-            yq = val(bits(y))
-            # identical rounding wherever y is not within 1e-9 (relative) of a rounding tie
-            step = 2.0 ** (np.floor(np.log2(np.abs(y) + 1e-300)) - 7)
-            frac = np.abs(y) / step % 1.0
-            safe = np.abs(frac - 0.5) > 1e-6
-            np.testing.assert_array_equal(out.y[k - 1][safe], yq[safe])
-            z = z + out.y[k - 1] @ val(W).T
+            if round_y:
+                yq = val(bits(y))
+                # identical rounding wherever y is not within 1e-9 (relative) of a rounding tie
+                step = 2.0 ** (np.floor(np.log2(np.abs(y) + 1e-300)) - 7)
+                frac = np.abs(y) / step % 1.0
+                safe = np.abs(frac - 0.5) > 1e-6
+                np.testing.assert_array_equal(out.y[k - 1][safe], yq[safe])
+                z = z + out.y[k - 1] @ val(W).T
+            else:
+                np.testing.assert_allclose(out.y[k - 1], y, rtol=1e-10, atol=1e-12)
+                z = z + y @ val(W).T
         lse = logsumexp(z, axis=1)
         conf = np.exp(z.max(1) - lse)
         np.testing.assert_array_equal(out.tok[k], z.argmax(1))
@@ -428,6 +449,43 @@ def test_chain_remask_and_reveal_control_flow():
 
 # ---- decode loop around the chain: recorded token, committed-token remask, commit, block decode ----
 
+@pytest.mark.parametrize("round_y,remask_mode,head_reveal", [(0, 0, 1), (1, 0, 1), (1, 1, 1), (0, 0, 0)])
+def test_chain_resumed_head_by_head_equals_full_run(round_y, remask_mode, head_reveal):
+    """A chain continued one head per call (state_offset = k - 1, run_state0 = 0, the previous call's
+    z / h_run / masks / cond_tok / protect_pos / x_tok as inputs) gives, on every output, what the
+    K-head call gives: the resumed form is what the GPU comparisons run the oracle in.  Straddling
+    inputs with remask on, so that reveals above the threshold, forced reveals and remasks all occur."""
+    cfg = mi.straddling(mi.config(0, B=7, L=8, V=640))
+    W, E = mi.lm_head(cfg), mi.embedding(cfg)
+    heads = [mi.head_weights(cfg, k) for k in range(cfg.K)]
+    z0, h = mi.logits0(cfg).astype(np.float64), val(mi.hidden(cfg))
+    kw = dict(tau=0.5, tau_remask=0.3 if head_reveal else 0.97, remask_mode=remask_mode, round_y=round_y,
+              head_reveal=head_reveal)
+    K = cfg.K
+    full = orc.chain_step(orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, K, **kw), E, W, heads, z0, h)
+    assert full.remasked.sum() > 0 and (full.revealed_at >= 0).sum() > cfg.B     # the case is not degenerate
+    o = orc.chain_step(orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 0, **kw), E, W, [], z0, h)
+    for f in ("tok", "conf", "lse", "gap", "remasked"):
+        np.testing.assert_array_equal(getattr(o, f)[0], getattr(full, f)[0])
+    np.testing.assert_array_equal(o.draft_pos[:, 0], full.draft_pos[:, 0])
+    np.testing.assert_array_equal(o.draft_tok[:, 0], full.draft_tok[:, 0])
+    for k in range(1, K + 1):
+        ck = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, fresh_block=0, state_offset=k - 1, run_state0=0, **kw)
+        o = orc.chain_step(ck, E, W, heads[k - 1:k], o.z, o.hrun, masked=o.masked, revealed_at=o.revealed_at,
+                           cond_tok=o.cond_tok, protect_pos=o.protect_pos, x_tok=o.x_tok)
+        for f in ("tok", "conf", "lse", "gap", "remasked"):
+            np.testing.assert_array_equal(getattr(o, f)[1], getattr(full, f)[k], err_msg=f"{f} state {k}")
+        np.testing.assert_array_equal(o.draft_pos[:, 1], full.draft_pos[:, k])
+        np.testing.assert_array_equal(o.draft_tok[:, 1], full.draft_tok[:, k])
+        assert np.all(o.draft_pos[:, 0] == -1)          # slot 0 of a resumed call is not written
+    for f in ("z", "hrun", "masked", "revealed_at", "cond_tok", "protect_pos", "x_tok"):
+        np.testing.assert_array_equal(getattr(o, f), getattr(full, f), err_msg=f)
+    # an independent replay of what the state index means: a row revealed at state s carries s
+    for s_idx in range(K + 1):
+        rows = full.revealed_at == s_idx
+        np.testing.assert_array_equal(full.x_tok[rows], full.tok[s_idx][rows])
+
+
 def test_token_prob_against_library_softmax():
     """softmax(z)[x_tok] via scipy; it never exceeds the top-1 probability and equals it at the argmax."""
     from scipy.special import softmax
@@ -558,6 +616,47 @@ def test_joint_candidate_verification_brute_force():
 
 # ---------------------------------------------------------------------------------------------
 # Training objective (Section 3.3, Equation 3)
+def test_build_candidates_hand_example_and_nesting():
+    """Figure 1 (d): candidate k = the block with the first k drafts written in.  A by-hand example,
+    then on random inputs: candidate 0 is the block itself, candidate k differs from candidate k - 1
+    exactly at draft k - 1's position (nothing if that draft is missing), masks are nested."""
+    MASK = 99
+    x_t = np.array([[5, -1, 7, -1, -1]], np.int32)
+    m_t = np.array([[0, 1, 0, 1, 1]], np.uint8)
+    dp = np.array([[3, 1, -1]], np.int32); dt = np.array([[40, 41, 42]], np.int32)
+    ct, cm = orc.build_candidates(x_t, m_t, dp, dt, MASK)
+    np.testing.assert_array_equal(ct[0], [[5, MASK, 7, MASK, MASK], [5, MASK, 7, 40, MASK], [5, 41, 7, 40, MASK],
+                                          [5, 41, 7, 40, MASK]])
+    np.testing.assert_array_equal(cm[0], [[0, 1, 0, 1, 1], [0, 1, 0, 0, 1], [0, 0, 0, 0, 1], [0, 0, 0, 0, 1]])
+    rng = np.random.default_rng(7)
+    B, L, K = 50, 16, 4
+    m_t = (rng.random((B, L)) < 0.7).astype(np.uint8)
+    x_t = rng.integers(0, 1000, (B, L)).astype(np.int32)
+    dp = np.full((B, K), -1, np.int32); dt = rng.integers(1000, 2000, (B, K)).astype(np.int32)
+    for b in range(B):                                   # drafts at distinct masked positions, some missing
+        free = rng.permutation(np.flatnonzero(m_t[b]))[:K]
+        dp[b, :len(free)] = free
+        dp[b, rng.random(K) < 0.15] = -1
+    ct, cm = orc.build_candidates(x_t, m_t, dp, dt, MASK)
+    np.testing.assert_array_equal(cm[:, 0], m_t)
+    np.testing.assert_array_equal(ct[:, 0], np.where(m_t == 1, MASK, x_t))
+    for k in range(1, K + 1):
+        for b in range(B):
+            diff = np.flatnonzero((ct[b, k] != ct[b, k - 1]) | (cm[b, k] != cm[b, k - 1]))
+            if dp[b, k - 1] < 0:
+                assert len(diff) == 0
+            else:
+                np.testing.assert_array_equal(diff, [dp[b, k - 1]])
+                assert ct[b, k, dp[b, k - 1]] == dt[b, k - 1] and cm[b, k, dp[b, k - 1]] == 0
+        assert np.all(cm[:, k] <= cm[:, k - 1])
+    assert np.all(ct[cm == 1] == MASK)
+    # in candidate j the position of draft j is still masked: what the joint verification reads there
+    for b in range(B):
+        for j in range(K):
+            if dp[b, j] >= 0:
+                assert cm[b, j, dp[b, j]] == 1
+
+
 def test_kl_loss_against_library_and_closed_forms():
     """KL(softmax(teacher) || softmax(student)) per row against scipy's softmax + rel_entr, a
     two-class closed form, shift invariance, and the zero at student = teacher + const."""
@@ -800,8 +899,11 @@ def test_transformer_head_body_composition():
     h = val(mi.hidden(cfg))
     ctok = np.array([3, 17, 60], np.int32)
     plen = np.array([0, 5, 2], np.int32)
-    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, tau=0.9)
+    oc = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, tau=0.9, round_y=1)
     u, y, h_after = orc.head_transformer(oc, tc, w1, layers, plen, g, E, ctok, h)
+    oc_plain = orc.make_cfg(cfg.d, cfg.V, cfg.B, cfg.L, 1, tau=0.9)
+    u_p, y_p, _ = orc.head_transformer(oc_plain, tc, w1, layers, plen, g, E, ctok, h)
+    np.testing.assert_array_equal(u_p, u)
     for b in range(cfg.B):
         rows = slice(b * cfg.L, (b + 1) * cfg.L)
         x = np.concatenate([h[rows], np.repeat(f(E[ctok[b]])[None], cfg.L, 0)], 1)
@@ -810,6 +912,7 @@ def test_transformer_head_body_composition():
             U = _np_layer(td, layers[l], U, int(plen[b]), b, 1e-6)
         np.testing.assert_allclose(u[rows], U, rtol=1e-9, atol=1e-12)
         yn = U / np.sqrt((U ** 2).mean(-1, keepdims=True) + 1e-6) * f(g)
+        np.testing.assert_allclose(y_p[rows], yn, rtol=1e-9, atol=1e-12)     # the definition: y not rounded
         yb = orc.bf16_round(yn)
         assert np.mean(y[rows] == yb) > 0.999          # (a rounding tie may flip under 1e-9 noise)
         np.testing.assert_allclose(y[rows], yb, rtol=2 ** -7)
