@@ -56,9 +56,12 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     const int cnt = rb_end - rb_begin;
     const int P = (cnt + LM_WAVES - 1) / LM_WAVES;
     const int n_lo = P ? cnt / P : 0, n_rem = P ? cnt % P : 0;
+    // (reverse: the passes walk the workgroup's range from its end, so that a launch starts on the
+    //  part of W_lm and z that the previous launch, walking forward, touched last)
     auto pass_rb = [&](int p, bool &active) -> int {
-        const int o = p * n_lo + (p < n_rem ? p : n_rem);
-        const int n = n_lo + (p < n_rem ? 1 : 0);
+        const int q = (a.reverse && p < P) ? P - 1 - p : p;
+        const int o = q * n_lo + (q < n_rem ? q : n_rem);
+        const int n = n_lo + (q < n_rem ? 1 : 0);
         active = (p < P) && (wave < n);
         return rb_begin + o + wave;
     };

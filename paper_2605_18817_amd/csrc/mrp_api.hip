@@ -548,6 +548,9 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             la.KB = d / 16; la.n_rb = (V + 31) / 32; la.nIb = c->nIb;
             la.M = M; la.V = V;
             la.nWG = c->nCU;
+            // consecutive heads walk the vocabulary in opposite directions: what the previous head
+            // touched last (W_lm is shared by all heads) is still in the L2s when this one starts
+            la.reverse = (off + k) & 1;
             la.z = z; la.pm = c->pm; la.ps = c->ps; la.pi = c->pi;
             HIP_TRY(c, launch_lm_persist(la, st));
             nT_lm = la.nWG;

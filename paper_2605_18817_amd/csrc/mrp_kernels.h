@@ -63,6 +63,7 @@ struct LmPersistArgs {
     int KB, n_rb, nIb;
     int M, V;
     int nWG;           // workgroups (one per CU)
+    int reverse;       // 1: every workgroup walks its vocabulary range from the end
     float *z;          // [M][V] in/out
     float *pm, *ps;    // partials [M][nWG]: one slot per workgroup, a row's slots contiguous
     int *pi;

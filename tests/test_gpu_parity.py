@@ -12,7 +12,7 @@ from harness import (Problem, compare_chain, dev_bits, gpu_chain, io_to_host, or
 pytestmark = pytest.mark.gpu
 
 
-def _free_run(cfg, rcfg, gamma="ones", share_heads=False, seqs=None, max_exempt_frac=0.25):
+def _free_run(cfg, rcfg, gamma="ones", share_heads=False, seqs=None, max_exempt=0):
     prob = Problem(cfg, gamma=gamma, share_heads=share_heads)
     try:
         z0 = mi.logits0(cfg)
@@ -23,8 +23,9 @@ def _free_run(cfg, rcfg, gamma="ones", share_heads=False, seqs=None, max_exempt_
         seqs = list(range(cfg.B)) if seqs is None else seqs
         rows = np.concatenate([np.arange(b * cfg.L, (b + 1) * cfg.L) for b in seqs])
         o = oracle_chain(prob, z0[rows], mi.bf16_bits_to_f64(h[rows]), rcfg, cfg.K)
-        stats = compare_chain(g, z_d.cpu().numpy()[rows], hrun_d.cpu().numpy()[rows], o.out, seqs, cfg.L, cfg.K,
-                              rcfg, max_exempt_frac=max_exempt_frac)
+        plain = oracle_chain(prob, z0[rows], mi.bf16_bits_to_f64(h[rows]), rcfg, cfg.K, round_y=0)
+        stats = compare_chain(g, z_d.cpu().numpy()[rows], hrun_d.cpu().numpy()[rows], o, seqs, cfg.L, cfg.K,
+                              rcfg, plain=plain, max_exempt=max_exempt)
         print(f"\n[{cfg.name or cfg.cid} d={cfg.d} V={cfg.V} M={cfg.M}] {stats}")
         return prob, g, o, stats
     except Exception:
@@ -204,7 +205,7 @@ def test_teacher_forced_heads_and_resume():
             g = io_to_host(io)
             o1 = oracle_chain(prob, s.z, s.hrun, r1, 1, masked=s.masked, revealed_at=s.revealed_at,
                               cond_tok=s.cond_tok, protect_pos=s.protect_pos, heads=prob.heads[k - 1:k], x_tok=s.x_tok)
-            stats = compare_chain(g, z_d.cpu().numpy(), hrun_d.cpu().numpy(), o1.out, seqs, cfg.L, 1, r1)
+            stats = compare_chain(g, z_d.cpu().numpy(), hrun_d.cpu().numpy(), o1, seqs, cfg.L, 1, r1)
             print(f"\n[teacher-forced head {k}] {stats}")
             np.testing.assert_array_equal(o1.out.tok[1], full.out.tok[k])
     finally:

@@ -9,7 +9,7 @@ import torch
 import mrp_inputs as mi
 import oracle as orc
 import paper_2605_18817_amd as mrp
-from harness import compare_chain, dev_bits, io_to_host
+from harness import compare_chain, dev_bits, io_to_host, oracle_chain
 
 pytestmark = pytest.mark.gpu
 
@@ -57,7 +57,7 @@ class TfProblem:
         self.ctx.close()
 
 
-def _run(cfg, td, rcfg, seqs=None, gain="normal", share=False, max_exempt_frac=0.25):
+def _run(cfg, td, rcfg, seqs=None, gain="normal", share=False, max_exempt=0):
     prob = TfProblem(cfg, td, gain=gain, share=share)
     try:
         z0 = mi.logits0(cfg)
@@ -71,17 +71,15 @@ def _run(cfg, td, rcfg, seqs=None, gain="normal", share=False, max_exempt_frac=0
         g = io_to_host(io)
         seqs = list(range(cfg.B)) if seqs is None else list(seqs)
         rows = np.concatenate([np.arange(b * cfg.L, (b + 1) * cfg.L) for b in seqs])
-        oc = orc.make_cfg(cfg.d, cfg.V, len(seqs), cfg.L, cfg.K, tau=rcfg.tau, r_min=rcfg.r_min,
-                          max_accept=rcfg.max_accept, carry_hidden=rcfg.carry_hidden, tau_remask=rcfg.tau_remask,
-                          head_reveal=rcfg.head_reveal, fresh_block=rcfg.fresh_block, state_offset=rcfg.state_offset,
-                          run_state0=rcfg.run_state0, remask_mode=rcfg.remask_mode)
         tc = orc.make_tcfg(td.D, td.n_heads, td.n_kv_heads, td.head_dim, td.d_ff, td.P_max, td.rope_theta)
         sub = [[dict(lay, kc=np.ascontiguousarray(lay["kc"][seqs]), vc=np.ascontiguousarray(lay["vc"][seqs]))
                 for lay in ls] for ls in prob.layers]
-        o = orc.chain_step(oc, prob.E, prob.W, [(w1, None, g_) for (w1, _, g_) in prob.heads], z0[rows],
-                           mi.bf16_bits_to_f64(h[rows]), tbody=orc.TBody(tc, sub, prob.plen[seqs]))
+        tb = orc.TBody(tc, sub, prob.plen[seqs])
+        heads = [(w1, None, g_) for (w1, _, g_) in prob.heads]
+        o = oracle_chain(prob, z0[rows], mi.bf16_bits_to_f64(h[rows]), rcfg, cfg.K, heads=heads, tbody=tb)
+        plain = oracle_chain(prob, z0[rows], mi.bf16_bits_to_f64(h[rows]), rcfg, cfg.K, heads=heads, tbody=tb, round_y=0)
         stats = compare_chain(g, z_d.cpu().numpy()[rows], hrun_d.cpu().numpy()[rows], o, seqs, cfg.L, cfg.K, rcfg,
-                              max_exempt_frac=max_exempt_frac)
+                              plain=plain, max_exempt=max_exempt)
         print(f"\n[tbody d={cfg.d} M={cfg.M} D={td.D} nh={td.n_heads}/{td.n_kv_heads} P<={td.P_max}] {stats}", flush=True)
         return stats
     finally:
@@ -126,7 +124,7 @@ def test_config1_shape_three_layers():
     of 128, gated MLP of 6144) and a 1024-position prefix cache; the oracle checks two sequences."""
     cfg = mi.config(1, K=1)
     td = mi.TBodyDims(D=3, n_heads=16, n_kv_heads=8, head_dim=128, d_ff=6144, P_max=1024)
-    _run(cfg, td, mrp.RevealCfg(tau=cfg.tau), seqs=[0, 31], gain="ones", max_exempt_frac=0.5)
+    _run(cfg, td, mrp.RevealCfg(tau=cfg.tau), seqs=[0, 31], gain="ones")
 
 
 def test_tbody_argument_errors():
