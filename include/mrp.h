@@ -225,6 +225,26 @@ int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const floa
                             uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
                             int32_t *correction_tok /* [B] */);
 
+/* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc): mrp_verify_accept without a context.  Same computation, arguments and
+ * outputs, with L and V passed in; the kernels' partial (max, argmax) array lives in a device array
+ * of fixed size inside the library (MRP_VERIFY_STATIC_MAX_ENTRIES entries of 8 bytes = 512 KiB on
+ * every GPU the library runs on, held until the process ends) instead of a context's workspace.
+ * The call allocates nothing and launches only kernels.  B * K * ceil(V / 8192) must not exceed
+ * MRP_VERIFY_STATIC_MAX_ENTRIES: a larger problem is refused with MRP_ERR_WORKSPACE and nothing is
+ * launched (config 3 of the benchmarks, B = 128, K = 3, V = 151936, needs 7296).  All calls on one GPU
+ * share that GPU's array: calls that overlap in time on one GPU (different streams or threads) race
+ * and must be serialised by the caller; calls on one stream are ordered and safe.  The array keeps the
+ * last call's contents; every entry a call reads it has written itself.  The array's address is looked
+ * up on a device's first call (or by mrp_create on that device): under stream capture make that first
+ * call before capturing.  Returns MRP_OK or a negative status (no context, so no message). */
+#define MRP_VERIFY_STATIC_MAX_ENTRIES 65536
+size_t mrp_verify_accept_static_scratch_bytes(void);
+int mrp_verify_accept_static(void *stream, int B, int L, int V, int K, const float *verify,
+                             const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride,
+                             uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
+                             int32_t *correction_tok /* [B] */);
+
 /* Transformer head body (Section 3.2: the head "fuses [hidden states and token
  * embeddings] via a learned projection, passes the result through a small
  * number of transformer layers, and reuses the backbone's language model

@@ -6,4 +6,4 @@ streams.  There is no CPU fallback: without the built library, or without a
 GPU, calls fail loudly.
 """
 from .binding import (MrpContext, RevealCfg, StepIO, Head, TLayer, load_library, library_path,  # noqa: F401
-                      MrpError, pack_weight, packed_bytes, EXPORTED_SYMBOLS)
+                      MrpError, pack_weight, packed_bytes, verify_accept_static, EXPORTED_SYMBOLS)

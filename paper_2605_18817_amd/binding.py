@@ -11,7 +11,7 @@ from . import build as _build
 EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
     "mrp_pack_weight", "mrp_pack_body_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms", "mrp_tbody_create", "mrp_chain_step_tf",
-    "mrp_profile_enable", "mrp_profile_read",
+    "mrp_profile_enable", "mrp_profile_read", "mrp_verify_accept_static", "mrp_verify_accept_static_scratch_bytes",
 ]
 
 MRP_MAX_HEADS = 16
@@ -97,6 +97,9 @@ def load_library():
                                C.c_void_p]
     lib.mrp_verify_accept.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.mrp_verify_accept_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.mrp_verify_accept_static_scratch_bytes.restype = C.c_size_t
     lib.mrp_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.mrp_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
     _lib = lib
@@ -135,6 +138,14 @@ def pack_weight(w, body: bool = False):
     if rc != 0:
         raise MrpError(f"mrp_pack_weight failed: {rc}")
     return out
+
+
+def verify_accept_static(B: int, L: int, V: int, K: int, verify, draft_pos, draft_tok, draft_stride: int, match,
+                         accept_len, correction_tok) -> int:
+    """mrp_verify_accept_static: no context, no allocation; returns the status code."""
+    return load_library().mrp_verify_accept_static(_stream(), B, L, V, K, _ptr(verify), _ptr(draft_pos),
+                                                   _ptr(draft_tok), draft_stride, _ptr(match), _ptr(accept_len),
+                                                   _ptr(correction_tok))
 
 
 @dataclass

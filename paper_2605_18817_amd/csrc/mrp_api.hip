@@ -197,6 +197,7 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     const Layout l = make_layout(dims, c->nCU);
     c->nIb = l.nIb; c->plane = l.plane; c->nT_max = l.nT_max; c->part_rows = l.part_rows; c->maxB = l.maxB;
     c->ws_bytes = l.total;
+    (void)verify_static_scratch();   // resolve this device's scratch address of mrp_verify_accept_static now
     if (stream_gemm_configure() != hipSuccess || lm_persist_configure() != hipSuccess) {
         delete c;
         return MRP_ERR_HIP;

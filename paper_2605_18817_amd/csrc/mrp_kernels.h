@@ -273,6 +273,7 @@ hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *ver
                          const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
                          int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
 int verify_chunks(int V);
+void *verify_static_scratch();   // current device's file-scope scratch of mrp_verify_accept_static (nullptr on failure)
 
 // transformer head body (tbody.hip)
 hipError_t tbody_configure();   // once per device
