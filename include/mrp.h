@@ -225,6 +225,38 @@ int mrp_verify_accept_joint(mrp_ctx *ctx, void *stream, int B, int K, const floa
                             uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
                             int32_t *correction_tok /* [B] */);
 
+/* Candidate blocks of the joint verification (Figure 1 (d)): candidate k (k = 0 .. K) of a sequence is
+ * its block x_t with the first k drafts written in and every other position as in x_t; the
+ * backbone scores all K + 1 candidates in one pass and mrp_verify_accept_joint checks draft j on
+ * candidate j, where draft j's position is still masked.
+ *   x_t       int32 [B][L]  tokens of the block before the drafting (ignored where masked_t = 1)
+ *   masked_t  uint8 [B][L]  1 = the position holds the mask token in x_t
+ *   draft_pos/draft_tok  int32 [B][K] with row stride draft_stride (>= K): the chain step's drafts in
+ *             draft order (columns 1..K of its draft arrays); pos < 0 = missing draft, adds nothing;
+ *             pos >= L is skipped and reported (MRP_FLAG_DRAFT_POS)
+ *   mask_token  token id written at masked positions
+ *   cand_tok  int32 [B][K+1][L] out,  cand_masked  uint8 [B][K+1][L] out (1 = still masked).
+ * K = 0 gives the block itself. */
+int mrp_build_candidates(mrp_ctx *ctx, void *stream, int B, int K, const int32_t *x_t, const uint8_t *masked_t,
+                         const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride, int32_t mask_token,
+                         int32_t *cand_tok, uint8_t *cand_masked);
+
+/* Device error word.  An index that lives in device memory cannot be validated on the host before a
+ * launch; a kernel that meets one out of range clamps or skips it (so that nothing faults) and sets a
+ * bit of the context's error word:
+ *   MRP_FLAG_COND_TOK    cond_tok[b] outside [0, V): clamped into the embedding table
+ *   MRP_FLAG_DRAFT_POS   a draft position >= L: taken as a missing draft
+ *   MRP_FLAG_PREFIX_LEN  prefix_len[b] outside [0, max_prefix]: clamped
+ *   MRP_FLAG_X_TOK       a recorded token >= V (remask_mode 1): clamped
+ * mrp_poll_error waits for `stream` (hipStreamSynchronize: not for use under stream capture), returns the
+ * bits set since the last poll (0 = none) and clears them, or a negative status; mrp_last_error then
+ * names the conditions. */
+#define MRP_FLAG_COND_TOK 1
+#define MRP_FLAG_DRAFT_POS 2
+#define MRP_FLAG_PREFIX_LEN 4
+#define MRP_FLAG_X_TOK 8
+int mrp_poll_error(mrp_ctx *ctx, void *stream);
+
 /* For callers that cannot allocate (code under HIP graph capture, tight serving loops, harnesses
  * that forbid hipMalloc): mrp_verify_accept without a context.  Same computation, arguments and
  * outputs, with L and V passed in; the kernels' partial (max, argmax) array lives in a device array

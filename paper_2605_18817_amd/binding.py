@@ -12,6 +12,7 @@ EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
     "mrp_pack_weight", "mrp_pack_body_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms", "mrp_tbody_create", "mrp_chain_step_tf",
     "mrp_profile_enable", "mrp_profile_read", "mrp_verify_accept_static", "mrp_verify_accept_static_scratch_bytes",
+    "mrp_build_candidates", "mrp_poll_error",
 ]
 
 MRP_MAX_HEADS = 16
@@ -100,6 +101,9 @@ def load_library():
     lib.mrp_verify_accept_static.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.mrp_verify_accept_static_scratch_bytes.restype = C.c_size_t
+    lib.mrp_build_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
+                                         C.c_void_p, C.c_int, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.mrp_poll_error.argtypes = [C.c_void_p, C.c_void_p]
     lib.mrp_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.mrp_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
     _lib = lib
@@ -331,6 +335,17 @@ class MrpContext:
                                               _ptr(draft_tok), draft_stride, _ptr(match), _ptr(accept_len),
                                               _ptr(correction_tok))
         return self._check(rc, "mrp_verify_accept_joint") if check else rc
+
+    def build_candidates(self, B: int, K: int, x_t, masked_t, draft_pos, draft_tok, draft_stride: int,
+                         mask_token: int, cand_tok, cand_masked, check: bool = True) -> int:
+        rc = self.lib.mrp_build_candidates(self._h, _stream(), B, K, _ptr(x_t), _ptr(masked_t), _ptr(draft_pos),
+                                           _ptr(draft_tok), draft_stride, mask_token, _ptr(cand_tok),
+                                           _ptr(cand_masked))
+        return self._check(rc, "mrp_build_candidates") if check else rc
+
+    def poll_error(self) -> int:
+        """Wait for the current stream; bits of the device error word set since the last poll (cleared)."""
+        return self._check(self.lib.mrp_poll_error(self._h, _stream()), "mrp_poll_error")
 
     def kl_loss(self, M: int, teacher, student, row_mask, scale: float, loss_rows, grad=None,
                 check: bool = True) -> int:

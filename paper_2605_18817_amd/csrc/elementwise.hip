@@ -50,10 +50,11 @@ __global__ __launch_bounds__(256) void init_hidden_kernel(const uint16_t *__rest
 
 __global__ __launch_bounds__(256) void gather_e_kernel(const uint16_t *__restrict__ E,
                                                        const int32_t *__restrict__ cond_tok, uint4 *__restrict__ xe,
-                                                       int nIb, int L, int d, int V) {
+                                                       int nIb, int L, int d, int V, int *err_flag) {
     const int b = blockIdx.x;
     const int C8 = d >> 3;
-    int tokc = cond_tok[b];  // caller contract: 0 <= cond_tok < V; clamp so a bad value cannot fault
+    int tokc = cond_tok[b];  // caller contract: 0 <= cond_tok < V; a bad value is clamped and reported
+    if ((tokc < 0 || tokc >= V) && threadIdx.x == 0 && err_flag) atomicOr(err_flag, ERR_COND_TOK);
     tokc = tokc < 0 ? 0 : (tokc >= V ? V - 1 : tokc);
     const uint4 *erow = reinterpret_cast<const uint4 *>(E + (size_t)tokc * d);
     for (int c8 = threadIdx.x; c8 < C8; c8 += 256) {
@@ -160,8 +161,8 @@ hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long pl
 }
 
 hipError_t launch_gather_e(const uint16_t *E, const int32_t *cond_tok, uint4 *xe, int nIb, int B, int L, int d,
-                           int V, hipStream_t st) {
-    hipLaunchKernelGGL(gather_e_kernel, dim3(B), dim3(256), 0, st, E, cond_tok, xe, nIb, L, d, V);
+                           int V, int *err_flag, hipStream_t st) {
+    hipLaunchKernelGGL(gather_e_kernel, dim3(B), dim3(256), 0, st, E, cond_tok, xe, nIb, L, d, V, err_flag);
     return hipGetLastError();
 }
 

@@ -33,6 +33,7 @@ struct mrp_ctx {
     float *kl_part, *kl_lse;   // KL loss: 5 partial arrays [max_rows * tiles], row log-sum-exps [2][max_rows]
     size_t kl_stride;
     double *rms_part;          // residual magnitudes: per-workgroup sums of squares
+    int *err_flag;             // device error word (MRP_FLAG_* bits), read and cleared by mrp_poll_error
     // transformer head body (mrp_tbody_create): its own allocation
     bool tb_on;
     mrp_tbody_dims tb;
@@ -61,7 +62,7 @@ struct Layout {
     int nT_max;
     size_t part_rows;
     int maxB;
-    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, off_klp, off_kll, off_rms, total;
+    size_t off_XH, off_XE, off_S, off_Y, off_PART, off_pm, off_ps, off_pi, off_vwm, off_vwi, off_klp, off_kll, off_rms, off_err, total;
     size_t kl_stride;
 };
 
@@ -100,6 +101,7 @@ Layout make_layout(const mrp_dims *dm, int nCU) {
     l.off_klp = take(5 * l.kl_stride * 4);
     l.off_kll = take((size_t)2 * dm->max_rows * 4);
     l.off_rms = take(residual_rms_part_bytes());
+    l.off_err = take(256);
     l.total = o;
     return l;
 }
@@ -202,8 +204,10 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
         delete c;
         return MRP_ERR_HIP;
     }
+    c->ws = nullptr;
     if (hipMalloc(reinterpret_cast<void **>(&c->ws), l.total) != hipSuccess ||
         hipMemset(c->ws, 0, l.total) != hipSuccess || hipDeviceSynchronize() != hipSuccess) {
+        if (c->ws) (void)hipFree(c->ws);
         delete c;
         return MRP_ERR_HIP;
     }
@@ -221,6 +225,7 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     c->kl_lse = reinterpret_cast<float *>(c->ws + l.off_kll);
     c->kl_stride = l.kl_stride;
     c->rms_part = reinterpret_cast<double *>(c->ws + l.off_rms);
+    c->err_flag = reinterpret_cast<int *>(c->ws + l.off_err);
     *out = c;
     return MRP_OK;
 }
@@ -415,6 +420,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
     sa.draft_stride = K + 1;
     sa.xe = c->XE; sa.nIb = c->nIb;
     sa.x_tok = io->x_tok; sa.remask_mode = cfg->remask_mode; sa.z = z;
+    sa.err_flag = c->err_flag;
 
     if (cfg->run_state0) {
         int nT0 = 0;
@@ -429,7 +435,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         sa.E = K > 0 ? Eb : nullptr;
         HIP_TRY(c, launch_merge_select(sa, st));
     } else if (K > 0) {
-        HIP_TRY(c, launch_gather_e(Eb, io->cond_tok, c->XE, c->nIb, B, L, d, V, st));
+        HIP_TRY(c, launch_gather_e(Eb, io->cond_tok, c->XE, c->nIb, B, L, d, V, c->err_flag, st));
     }
     if (K == 0) return MRP_OK;
 
@@ -476,7 +482,8 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             const size_t part_d = c->part_rows * (size_t)d;
             hipError_t ge = hipSuccess;
             if (k == 1)
-                HIP_TRY(c, launch_rope_table(prefix_len, B, L, tb.max_prefix, (double)tb.rope_theta, c->tb_rope, st));
+                HIP_TRY(c, launch_rope_table(prefix_len, B, L, tb.max_prefix, (double)tb.rope_theta, c->tb_rope,
+                                             c->err_flag, st));
             // u_0 = fuse projection; planes <- RMSNorm(u_0) g1 of layer 0
             int nks = nks1;
             for (int l = 0; l < tb.D; ++l) {
@@ -648,7 +655,7 @@ static int verify_impl(mrp_ctx *c, void *stream, int B, int K, int joint, const 
     if (c->dims.V % 4 == 0 && !aligned16(verify)) return fail(c, MRP_ERR_ALIGN, "verify must be 16-byte aligned");
     if (B == 0) return MRP_OK;
     HIP_TRY(c, launch_verify(B, c->dims.block_len, c->dims.V, K, joint, verify, draft_pos, draft_tok, draft_stride, c->vwm,
-                             c->vwi, match, accept_len, correction_tok, static_cast<hipStream_t>(stream)));
+                             c->vwi, match, accept_len, correction_tok, c->err_flag, static_cast<hipStream_t>(stream)));
     return MRP_OK;
 }
 
@@ -664,6 +671,38 @@ int mrp_verify_accept_joint(mrp_ctx *c, void *stream, int B, int K, const float 
                             int32_t *correction_tok) {
     return verify_impl(c, stream, B, K, 1, verify, draft_pos, draft_tok, draft_stride, match, accept_len,
                        correction_tok);
+}
+
+int mrp_build_candidates(mrp_ctx *c, void *stream, int B, int K, const int32_t *x_t, const uint8_t *masked_t,
+                         const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride, int32_t mask_token,
+                         int32_t *cand_tok, uint8_t *cand_masked) {
+    if (!c) return MRP_ERR_NULL;
+    if (!x_t || !masked_t || !draft_pos || !draft_tok || !cand_tok || !cand_masked)
+        return fail(c, MRP_ERR_NULL, "mrp_build_candidates: NULL pointer");
+    if (B < 0 || B > c->maxB || K < 0 || K > MRP_MAX_HEADS || draft_stride < K)
+        return fail(c, MRP_ERR_SHAPE, "mrp_build_candidates: B=%d K=%d stride=%d out of range", B, K, draft_stride);
+    if (B == 0) return MRP_OK;
+    HIP_TRY(c, launch_build_candidates(B, c->dims.block_len, K, x_t, masked_t, draft_pos, draft_tok, draft_stride,
+                                       mask_token, cand_tok, cand_masked, c->err_flag,
+                                       static_cast<hipStream_t>(stream)));
+    return MRP_OK;
+}
+
+int mrp_poll_error(mrp_ctx *c, void *stream) {
+    if (!c) return MRP_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int flags = 0;
+    HIP_TRY(c, hipStreamSynchronize(st));
+    HIP_TRY(c, hipMemcpy(&flags, c->err_flag, sizeof(int), hipMemcpyDeviceToHost));
+    if (flags) {
+        HIP_TRY(c, hipMemset(c->err_flag, 0, sizeof(int)));
+        snprintf(c->err, sizeof(c->err), "device error word 0x%x:%s%s%s%s", flags,
+                 (flags & MRP_FLAG_COND_TOK) ? " cond_tok out of range (clamped)" : "",
+                 (flags & MRP_FLAG_DRAFT_POS) ? " draft position >= block length (taken as missing)" : "",
+                 (flags & MRP_FLAG_PREFIX_LEN) ? " prefix_len outside [0, max_prefix] (clamped)" : "",
+                 (flags & MRP_FLAG_X_TOK) ? " recorded token >= V (clamped)" : "");
+    }
+    return flags;
 }
 
 }  // extern "C"

@@ -88,6 +88,10 @@ struct TiledGemmArgs {
     int *pi;
 };
 
+// Bits of a context's device error word (the MRP_FLAG_* values of include/mrp.h): an index the caller
+// passed in device memory was out of range; the kernel clamped or skipped it and reports it here.
+enum { ERR_COND_TOK = 1, ERR_DRAFT_POS = 2, ERR_PREFIX_LEN = 4, ERR_X_TOK = 8 };
+
 // row-reduction partial: running max, sum of exp(x - max), index of the max
 struct Part {
     float m, s;
@@ -224,7 +228,7 @@ hipError_t launch_pack_weight(const uint16_t *src, int rows, int cols, uint4 *ds
 hipError_t launch_init_hidden(const uint16_t *h, float *hrun, uint4 *xh, long plane_stride, int nIb,
                               int M, int d, bool from_h, hipStream_t st);
 hipError_t launch_gather_e(const uint16_t *E, const int32_t *cond_tok, uint4 *xe, int nIb, int B, int L,
-                           int d, int V, hipStream_t st);
+                           int d, int V, int *err_flag, hipStream_t st);
 hipError_t launch_silu_split(const float *part, int nKs, uint4 *s_planes, long plane_stride, int nIb,
                              int M, int d, hipStream_t st);
 // u = (resid ? resid : 0) + sum of partials; y = bf16(RMSNorm(u) gamma); carry: hrun += u and its planes
@@ -259,6 +263,7 @@ struct SelectArgs {
     const uint16_t *E;      // embedding rows to gather for the next head (nullptr: skip)
     uint4 *xe;
     int nIb;
+    int *err_flag;          // device error word (may be nullptr)
 };
 hipError_t launch_reduce_rows(const float *z, int M, int V, float *pm, float *ps, int *pi, int *nT_out,
                               hipStream_t st);
@@ -271,7 +276,11 @@ hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_r
                          uint8_t *remasked, hipStream_t st);
 hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *verify, const int32_t *draft_pos,
                          const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
-                         int32_t *accept_len, int32_t *correction_tok, hipStream_t st);
+                         int32_t *accept_len, int32_t *correction_tok, int *err_flag, hipStream_t st);
+hipError_t launch_build_candidates(int B, int L, int K, const int32_t *x_t, const uint8_t *masked_t,
+                                   const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride,
+                                   int32_t mask_token, int32_t *cand_tok, uint8_t *cand_masked, int *err_flag,
+                                   hipStream_t st);
 int verify_chunks(int V);
 void *verify_static_scratch();   // current device's file-scope scratch of mrp_verify_accept_static (nullptr on failure)
 
@@ -279,7 +288,7 @@ void *verify_static_scratch();   // current device's file-scope scratch of mrp_v
 hipError_t tbody_configure();   // once per device
 bool tbody_shape_ok(int nh, int nkv, int head_dim, int L);
 hipError_t launch_rope_table(const int32_t *prefix_len, int B, int L, int P_max, double theta, float2 *out,
-                             hipStream_t st);
+                             int *err_flag, hipStream_t st);
 hipError_t launch_resid_norm_split(const float *part, int nKs, const float *resid, float *stream,
                                    const uint16_t *gain, float eps, uint4 *planes, long plane_stride, int nIb, int M,
                                    int d, hipStream_t st);

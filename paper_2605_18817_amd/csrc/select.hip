@@ -239,6 +239,7 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
                 if (a.remask_mode == 1 && r >= 0 && r <= a.state - 1) {
                     // probability of the token that was revealed here under the updated logits
                     int t = s_xtok[p];
+                    if (t >= a.V && a.err_flag) atomicOr(a.err_flag, ERR_X_TOK);
                     t = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
                     cr = (s_xtok[p] >= 0) ? expf(a.z[(size_t)(b * L + p) * a.V + t] - s_lse[p]) : 0.f;
                 }
@@ -260,7 +261,8 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
     }
     if (a.E != nullptr) {  // embedding row that conditions the next head
         const int C8 = a.d >> 3;
-        int tokc = s_gather;  // caller contract: 0 <= cond_tok < V; clamp so a bad value cannot fault
+        int tokc = s_gather;  // caller contract: 0 <= cond_tok < V; a bad value is clamped and reported
+        if ((tokc < 0 || tokc >= a.V) && threadIdx.x == 0 && a.err_flag) atomicOr(a.err_flag, ERR_COND_TOK);
         tokc = tokc < 0 ? 0 : (tokc >= a.V ? a.V - 1 : tokc);
         const uint4 *erow = reinterpret_cast<const uint4 *>(a.E + (size_t)tokc * a.d);
         for (int c8 = threadIdx.x; c8 < C8; c8 += 256) {
@@ -313,13 +315,17 @@ template <bool VEC4>
 __global__ __launch_bounds__(256) void verify_argmax_kernel(int L, int V, int K, int joint,
                                                             const float *__restrict__ verify,
                                                             const int32_t *__restrict__ draft_pos, int draft_stride,
-                                                            int nC, float *__restrict__ wm, int *__restrict__ wi) {
+                                                            int nC, float *__restrict__ wm, int *__restrict__ wi,
+                                                            int *err_flag) {
     __shared__ float sm[4], ss[4];
     __shared__ int si[4];
     const int c = blockIdx.x, bk = blockIdx.y;
     const int b = bk / K, j = bk % K;
     int pos = draft_pos[(size_t)b * draft_stride + j];
-    if (pos >= L) pos = -1;  // caller contract: pos < L; an invalid position counts as a missing draft
+    if (pos >= L) {  // caller contract: pos < L; an invalid position counts as a missing draft and is reported
+        if (threadIdx.x == 0 && c == 0 && err_flag) atomicOr(err_flag, ERR_DRAFT_POS);
+        pos = -1;
+    }
     Part p = part_identity();
     if (pos >= 0) {  // uniform over the workgroup
         // joint: [B][K+1][L][V], draft j reads candidate j; else one [B][L][V] tensor
@@ -383,7 +389,41 @@ __global__ __launch_bounds__(256) void verify_accept_kernel(int B, int K, int nC
     correction_tok[b] = corr;
 }
 
+// Candidate blocks of the joint verification (paper Figure 1 (d)): candidate k of a sequence is its
+// block x_t with the first k drafts written in.  One workgroup per sequence, one lane per position.
+__global__ __launch_bounds__(64) void build_candidates_kernel(int L, int K, const int32_t *__restrict__ x_t,
+                                                              const uint8_t *__restrict__ masked_t,
+                                                              const int32_t *__restrict__ draft_pos,
+                                                              const int32_t *__restrict__ draft_tok, int draft_stride,
+                                                              int32_t mask_token, int32_t *__restrict__ cand_tok,
+                                                              uint8_t *__restrict__ cand_masked, int *err_flag) {
+    const int b = blockIdx.x, p = threadIdx.x;
+    if (p >= L) return;
+    const uint8_t m0 = masked_t[(size_t)b * L + p] ? 1 : 0;
+    int32_t tok = m0 ? mask_token : x_t[(size_t)b * L + p];
+    uint8_t m = m0;
+    for (int k = 0; k <= K; ++k) {
+        if (k > 0) {   // candidate k adds draft k - 1
+            const int pos = draft_pos[(size_t)b * draft_stride + k - 1];
+            if (pos >= L && p == 0 && err_flag) atomicOr(err_flag, ERR_DRAFT_POS);
+            if (pos == p) { tok = draft_tok[(size_t)b * draft_stride + k - 1]; m = 0; }
+        }
+        const size_t o = ((size_t)b * (K + 1) + k) * L + p;
+        cand_tok[o] = tok;
+        cand_masked[o] = m;
+    }
+}
+
 }  // namespace
+
+hipError_t launch_build_candidates(int B, int L, int K, const int32_t *x_t, const uint8_t *masked_t,
+                                   const int32_t *draft_pos, const int32_t *draft_tok, int draft_stride,
+                                   int32_t mask_token, int32_t *cand_tok, uint8_t *cand_masked, int *err_flag,
+                                   hipStream_t st) {
+    hipLaunchKernelGGL(build_candidates_kernel, dim3(B), dim3(64), 0, st, L, K, x_t, masked_t, draft_pos, draft_tok,
+                       draft_stride, mask_token, cand_tok, cand_masked, err_flag);
+    return hipGetLastError();
+}
 
 int reduce_rows_tiles(int V) { return (V + RT - 1) / RT; }
 int verify_chunks(int V) { return (V + RT - 1) / RT; }
@@ -420,14 +460,14 @@ hipError_t launch_remask(int B, int L, int state, const float *conf, float tau_r
 
 hipError_t launch_verify(int B, int L, int V, int K, int joint, const float *verify, const int32_t *draft_pos,
                          const int32_t *draft_tok, int draft_stride, float *wm, int *wi, uint8_t *match,
-                         int32_t *accept_len, int32_t *correction_tok, hipStream_t st) {
+                         int32_t *accept_len, int32_t *correction_tok, int *err_flag, hipStream_t st) {
     const int nC = verify_chunks(V);
     if (V % 4 == 0)
         hipLaunchKernelGGL(verify_argmax_kernel<true>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, joint, verify,
-                           draft_pos, draft_stride, nC, wm, wi);
+                           draft_pos, draft_stride, nC, wm, wi, err_flag);
     else
         hipLaunchKernelGGL(verify_argmax_kernel<false>, dim3(nC, B * K), dim3(256), 0, st, L, V, K, joint, verify,
-                           draft_pos, draft_stride, nC, wm, wi);
+                           draft_pos, draft_stride, nC, wm, wi, err_flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(verify_accept_kernel, dim3((B + 255) / 256), dim3(256), 0, st, B, K, nC, wm, wi,

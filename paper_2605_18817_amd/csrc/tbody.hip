@@ -23,13 +23,15 @@ inline unsigned blocks_for(size_t n) { return (unsigned)((n + 255) / 256); }
 
 // cos / sin of pos * theta^(-2j/HD) for every row and j < HD/2, evaluated in fp64
 __global__ __launch_bounds__(256) void rope_table_kernel(const int32_t *__restrict__ prefix_len, int B, int L,
-                                                         int P_max, double theta, float2 *__restrict__ out) {
+                                                         int P_max, double theta, float2 *__restrict__ out,
+                                                         int *err_flag) {
     const size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= (size_t)B * L * (HD / 2)) return;
     const int j = (int)(idx % (HD / 2));
     const int row = (int)(idx / (HD / 2));
     const int b = row / L, i = row % L;
     int P = prefix_len[b];
+    if ((P < 0 || P > P_max) && i == 0 && j == 0 && err_flag) atomicOr(err_flag, ERR_PREFIX_LEN);   // clamped and reported
     P = P < 0 ? 0 : (P > P_max ? P_max : P);
     const double ang = (double)(P + i) * pow(theta, -2.0 * (double)j / (double)HD);
     out[idx] = make_float2((float)cos(ang), (float)sin(ang));
@@ -497,9 +499,9 @@ bool tbody_shape_ok(int nh, int nkv, int head_dim, int L) {
 }
 
 hipError_t launch_rope_table(const int32_t *prefix_len, int B, int L, int P_max, double theta, float2 *out,
-                             hipStream_t st) {
+                             int *err_flag, hipStream_t st) {
     hipLaunchKernelGGL(rope_table_kernel, dim3(blocks_for((size_t)B * L * (HD / 2))), dim3(256), 0, st, prefix_len,
-                       B, L, P_max, theta, out);
+                       B, L, P_max, theta, out, err_flag);
     return hipGetLastError();
 }
 

@@ -64,7 +64,7 @@ int mrp_verify_accept_static(void *stream, int B, int L, int V, int K, const flo
     int *wi = reinterpret_cast<int *>(static_cast<unsigned char *>(p) + SCRATCH_ENTRIES * sizeof(float));
     // every entry the second kernel reads is written by the first: nothing has to start at zero
     return launch_verify(B, L, V, K, 0, verify, draft_pos, draft_tok, draft_stride, wm, wi, match, accept_len,
-                         correction_tok, static_cast<hipStream_t>(stream)) == hipSuccess
+                         correction_tok, nullptr, static_cast<hipStream_t>(stream)) == hipSuccess
                ? MRP_OK
                : MRP_ERR_HIP;
 }
