@@ -4,12 +4,14 @@
 A "step" is one denoising step's whole chain on one synthetic batch: state 0
 (reduce the prior logits, reveal) and K heads (head MLP, shared LM head with
 residual add and fused split-vocabulary reduction, merge / reveal / draft
-[/ remask]).  Default workload: the SDAR-1.7B-shaped drafting configuration
-(d=2048, V=151936, B=32, block 4 -> 128 rows, K=3), whose LM-head kernel is
+[/ remask]).  Default workload: the largest configuration (d=4096, V=151936,
+B=256, block 16 -> 4096 rows, K=3, remask on), whose LM-head kernel is MFMA-bound;
+the same line carries, in its "config1_hbm_regime" sub-object, the SDAR-1.7B-shaped
+drafting configuration (d=2048, B=32, block 4 -> 128 rows), whose LM-head kernel is
 HBM-bound.  Inputs are seeded and synthetic and resident in HBM before the timed
 region.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1] [--skip-cpu-baseline]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--skip-cpu-baseline]
 
 Further workloads of the same library, each printing its own JSON line in the same format
 (--workload kl_loss | residual_rms | tbody): the training objective (forward + gradient), the
@@ -72,7 +74,7 @@ def _line(metric, value, unit, args, elapsed, dtype, workload, roof, cpu):
 
 def bench_kl_loss(args, np, torch, mi, mrp) -> dict:
     """Equation 3 forward + gradient on config-2-sized logits (1024 rows x 151936)."""
-    cfg = mi.CONFIGS[args.config if args.config != 1 else 2]
+    cfg = mi.CONFIGS[args.config if args.config not in (None, 1) else 2]
     M, V = cfg.M, cfg.V
     t = mi.logits0(cfg, step=1)
     s = t + mi.residual(cfg)
@@ -113,12 +115,16 @@ def bench_residual_rms(args, np, torch, mi, mrp) -> dict:
     pair = torch.empty((nb, S, S), dtype=torch.float64, device="cuda")
     delta = torch.empty((S,), dtype=torch.float64, device="cuda")
     elapsed, ev = _time_steps(torch, lambda: ctx.residual_rms(nb, S, N, X_d, False, pair, delta), args.warmup, args.steps)
+    # By the published peaks the kernel is HBM-bound: every state is read once (4 S N bytes per block,
+    # 165 us at 8 TB/s for this workload) against 442 fp64 flop per entry (109 us at 78.6 TFLOP/s).
+    byt = 4.0 * nb * S * N
     flop = (136 + 2 * 153) * float(nb) * N       # per entry: 136 fp64 subtractions, 153 fused multiply-adds
-    ach = flop / (ev / args.steps) / 1e12
-    roof = {"bound": "alu", "achieved": ach, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": ach / FP64_VECTOR_PEAK_TFLOPS, "traffic": traffic_from_profile(None, "residual_rms_pmc.txt"),
-            "kernel": "rms_partial_kernel<17>",
-            "kernel_ms": 1e3 * ev / args.steps, "hbm_GBps": 4.0 * nb * S * N / (ev / args.steps) / 1e9}
+    ach = byt / (ev / args.steps) / 1e9
+    roof = {"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+            "traffic": traffic_from_profile(None, "residual_rms_pmc.txt"),
+            "traffic_source": "profiles/residual_rms_pmc.txt (an earlier run of this command under rocprofv3 --pmc)",
+            "kernel": "rms_partial_kernel<17>", "kernel_ms": 1e3 * ev / args.steps,
+            "fp64_TFLOPs": flop / (ev / args.steps) / 1e12, "fp64_frac_of_78.6": flop / (ev / args.steps) / 1e12 / FP64_VECTOR_PEAK_TFLOPS}
     cpu = None
     if not args.skip_cpu_baseline:
         import oracle as orc
@@ -130,7 +136,7 @@ def bench_residual_rms(args, np, torch, mi, mrp) -> dict:
         cpu = {"value": (n / N) / (c1 - c0), "unit": "blocks/s", "cores": 1, "kind": "oracle",
                "sample": f"first {n} of {N} entries of one block's 17 states, {c1 - c0:.1f} s wall, fp64, gcc -O2"}
     ctx.close()
-    return _line("residual-magnitude blocks/s (App. B: 17 states of 16 x V logits) on 1 GPU; % fp64 vector roofline",
+    return _line("residual-magnitude blocks/s (App. B: 17 states of 16 x V logits) on 1 GPU; % HBM roofline",
                  nb * args.steps / elapsed, "blocks/s", args, elapsed, "f64",
                  f"{nb} blocks x 17 states x {N} fp32 entries (random-walk stand-in states)", roof, cpu)
 
@@ -192,39 +198,31 @@ def bench_tbody(args, np, torch, mi, mrp) -> dict:
                  f"prefix lengths uniform in [0, 1024]", roof, cpu)
 
 
-def main() -> int:
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody"],
-                    help="chain (default): the headline metric; the others time further entry points")
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--config", type=int, default=1, help="benchmark configuration 0..4")
-    ap.add_argument("--skip-cpu-baseline", action="store_true")
-    ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on exactly one GPU (sequences would shard by rows, the vocabulary by "
-              "columns with one small all-gather per head; neither is built); use --gpus 1", file=sys.stderr)
-        return 2
+def host_cpu_info():
+    """CPU model and physical core count of the host (from /proc/cpuinfo)."""
+    model, cores = "unknown", set()
+    try:
+        phys = core = None
+        with open("/proc/cpuinfo") as f:
+            for ln in f:
+                if ln.startswith("model name") and model == "unknown":
+                    model = ln.split(":", 1)[1].strip()
+                elif ln.startswith("physical id"):
+                    phys = ln.split(":", 1)[1].strip()
+                elif ln.startswith("core id"):
+                    core = ln.split(":", 1)[1].strip()
+                elif not ln.strip():
+                    if phys is not None and core is not None:
+                        cores.add((phys, core))
+                    phys = core = None
+    except OSError:
+        pass
+    return model, (len(cores) or None)
 
-    import numpy as np
-    import torch
 
-    import mrp_inputs as mi
-    import paper_2605_18817_amd as mrp
-
-    if not torch.cuda.is_available():
-        print("bench.py: no GPU; the MRP chain has no CPU path", file=sys.stderr)
-        return 3
-
-    if args.workload != "chain":
-        fn = {"kl_loss": bench_kl_loss, "residual_rms": bench_residual_rms, "tbody": bench_tbody}[args.workload]
-        print(json.dumps(fn(args, np, torch, mi, mrp)))
-        return 0
-
-    cfg = mi.CONFIGS[args.config]
+def run_chain_config(cfg, args, np, torch, mi, mrp) -> dict:
+    """Time `args.steps` chain steps of one benchmark configuration (inputs resident in HBM), the
+    LM-head kernel bracketed by HIP events on the launch stream, and the oracle on a bounded sample."""
     d, V, B, L, K, M = cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, cfg.M
 
     def dev_bits(a):
@@ -243,8 +241,10 @@ def main() -> int:
                for (w1, w2, g) in heads_h]
     h_bits = mi.hidden(cfg)
     h_d = dev_bits(h_bits)
+    ns = min(B, max(1, int(os.environ.get("MRP_BENCH_ORACLE_SEQS", "32" if d <= 2048 else "8"))))
     z0 = mi.logits0(cfg)
     z_d = torch.from_numpy(z0).cuda()
+    z0 = np.ascontiguousarray(z0[:ns * L])          # the oracle's sample; the rest of the host copy is dropped
     hrun_d = torch.zeros((M, d), dtype=torch.float32, device="cuda")
     io = mrp.StepIO(B, L, K)
     rcfg = mrp.RevealCfg(tau=cfg.tau, tau_remask=cfg.tau_remask, fresh_block=1)
@@ -275,6 +275,7 @@ def main() -> int:
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
+        del src, dst
 
     # ---- roofline of the dominant kernel (LM head + residual add + fused reduction) ----
     lm_avg_ms = float(np.mean(lm_ms)) if lm_ms else float("nan")
@@ -290,51 +291,110 @@ def main() -> int:
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS}
     roof["traffic"] = traffic_from_profile(cfg.cid)
+    roof["traffic_source"] = (f"profiles/lm_head_cfg{cfg.cid}_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier "
+                              "run of this command, scaled by what the counters read for a 1 GiB copy; not measured in this run"
+                              if roof["traffic"] is not None else None)
     roof["kernel"] = ("lm_persist_kernel" if M <= 128 and V % 4 == 0 else
                       "tiled_gemm_kernel<EPI_LM>" if M >= 768 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
     roof["kernel_ms"] = lm_avg_ms
     roof["launches"] = len(lm_ms)
+    roof["algorithmic_bytes_per_launch"] = lm_bytes
+    roof["flop_per_launch"] = lm_flops
     roof["lm_head_share_of_step"] = (lm_avg_ms * K) / ms_per_step
 
     # ---- the oracle, as it stands, on the host cores (bounded sample of whole sequences) ----
     cpu = None
     if not args.skip_cpu_baseline:
         import oracle as orc
-        ns = min(B, max(1, int(os.environ.get("MRP_BENCH_ORACLE_SEQS", "16" if d <= 2048 else "2"))))
-        seqs = list(range(ns))
-        rows = np.concatenate([np.arange(b * L, (b + 1) * L) for b in seqs])
+        rows = np.arange(ns * L)
         oc = orc.make_cfg(d, V, ns, L, K, tau=cfg.tau, tau_remask=cfg.tau_remask)
         zz = z0[rows].astype(np.float64)
         hh = mi.bf16_bits_to_f64(h_bits[rows])
         c0 = time.perf_counter()
         orc.chain_step(oc, E, W, heads_h, zz, hh)
         c1 = time.perf_counter()
+        model, phys = host_cpu_info()
         cpu = {"value": len(rows) * K / (c1 - c0), "unit": "tokens/s", "cores": orc.threads(), "kind": "oracle",
-               "sample": f"{ns} of {B} sequences ({len(rows)} rows x {K} heads) of the same workload, "
-                         f"{c1 - c0:.1f} s wall, fp64, gcc -O2 -fopenmp"}
+               "physical_cores": phys, "cpu_model": model,
+               "sample": f"first {ns} of {B} sequences ({len(rows)} rows x {K} heads) of the same workload, "
+                         f"{c1 - c0:.1f} s wall, fp64, gcc -O2 -fopenmp, {orc.threads()} OpenMP threads"}
+    ctx.close()
+    workload = (f"config {cfg.cid} ({cfg.name}): d={d} V={V} B={B} block={L} rows={M} K={K} "
+                f"tau={cfg.tau}" + (f" tau_remask={cfg.tau_remask}" if cfg.tau_remask >= 0 else ""))
+    del z_d, Wp_d, E_d, heads_d, h_d, hrun_d, io
+    torch.cuda.empty_cache()
+    return {"workload": workload, "value": tokens_per_s, "unit": "tokens/s", "ms_per_step": ms_per_step,
+            "roofline": roof, "cpu_baseline": cpu}
 
-    out = {
+
+def chain_line(res: dict, args) -> dict:
+    return {
         "metric": "MRP draft tokens/sec per step (B\u00d7block\u00d7K) on 1 GPU; % HBM/MFMA roofline",
-        "value": tokens_per_s,
+        "value": res["value"],
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": ms_per_step,
+        "ms_per_step": res["ms_per_step"],
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": f"config {cfg.cid} ({cfg.name}): d={d} V={V} B={B} block={L} rows={M} K={K} "
-                               f"tau={cfg.tau}" + (f" tau_remask={cfg.tau_remask}" if cfg.tau_remask >= 0 else ""),
+        "config": {"workload": res["workload"],
                    "accumulate": "fp32", "logit_state": "fp32", "lm_head_operands": "bf16",
                    "head_body_operands": "fp32 activations as two fp16 terms, bf16 weights converted to fp16"},
-        "roofline": roof,
-        "cpu_baseline": cpu,
+        "roofline": res["roofline"],
+        "cpu_baseline": res["cpu_baseline"],
     }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody"],
+                    help="chain (default): the headline metric; the others time further entry points")
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--config", type=int, default=None,
+                    help="time one benchmark configuration 0..4 only (default: configuration 4 as the line, "
+                         "configuration 1 in its config1_hbm_regime sub-object)")
+    ap.add_argument("--skip-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (sequences would shard by rows, the vocabulary by "
+              "columns with one small all-gather per head; neither is built); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import mrp_inputs as mi
+    import paper_2605_18817_amd as mrp
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU; the MRP chain has no CPU path", file=sys.stderr)
+        return 3
+
+    if args.workload != "chain":
+        fn = {"kl_loss": bench_kl_loss, "residual_rms": bench_residual_rms, "tbody": bench_tbody}[args.workload]
+        print(json.dumps(fn(args, np, torch, mi, mrp)))
+        return 0
+
+    if args.config is not None:
+        res = run_chain_config(mi.CONFIGS[args.config], args, np, torch, mi, mrp)
+        print(json.dumps(chain_line(res, args)))
+        return 0
+    # default: the largest configuration (MFMA-bound) is the line; the SDAR-1.7B-shaped configuration
+    # (HBM-bound LM head) rides along in a sub-object with its own step time, roofline and oracle baseline
+    big = run_chain_config(mi.CONFIGS[4], args, np, torch, mi, mrp)
+    small = run_chain_config(mi.CONFIGS[1], args, np, torch, mi, mrp)
+    out = chain_line(big, args)
+    out["config1_hbm_regime"] = {k: small[k] for k in ("workload", "value", "unit", "ms_per_step", "roofline",
+                                                          "cpu_baseline")}
     print(json.dumps(out))
-    ctx.close()
     return 0
 
 
