@@ -146,7 +146,7 @@ def bench_tbody(args, np, torch, mi, mrp) -> dict:
     (16 query / 8 kv heads of 128, gated MLP 6144), prefix caches of 1024 positions, one module applied K times."""
     cfg = mi.CONFIGS[1]
     d, V, B, L, K, M = cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, cfg.M
-    td = mi.TBodyDims(D=3, n_heads=16, n_kv_heads=8, head_dim=128, d_ff=6144, P_max=1024)
+    td = mi.TBodyDims(D=args.depth, n_heads=16, n_kv_heads=8, head_dim=128, d_ff=6144, P_max=1024)
     bits = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
     W, E = mi.lm_head(cfg), mi.embedding(cfg)
     w1, _, g = mi.head_weights(cfg, 0)
@@ -192,9 +192,10 @@ def bench_tbody(args, np, torch, mi, mrp) -> dict:
         cpu = {"value": len(rows) * K / (c1 - c0), "unit": "tokens/s", "cores": orc.threads(), "kind": "oracle",
                "sample": f"sequences 0 and {B - 1} of {B} ({len(rows)} rows x {K} heads), {c1 - c0:.1f} s wall, fp64"}
     ctx.close()
-    return _line("MRP draft tokens/sec per step with the transformer head body (D=3) on 1 GPU; % HBM roofline of the LM head",
+    roof["body_ms_per_head"] = (1e3 * elapsed / args.steps - lm_avg * K) / K      # everything of a head but its LM-head kernel
+    return _line(f"MRP draft tokens/sec per step with the transformer head body (D={td.D}) on 1 GPU; % HBM roofline of the LM head",
                  M * K * args.steps / elapsed, "tokens/s", args, elapsed, "bf16",
-                 f"config 1 sizes (d={d} V={V} B={B} block={L} K={K}), head body: 3 layers, 16/8 heads of 128, d_ff 6144, "
+                 f"config 1 sizes (d={d} V={V} B={B} block={L} K={K}), head body: {td.D} layers, 16/8 heads of 128, d_ff 6144, "
                  f"prefix lengths uniform in [0, 1024]", roof, cpu)
 
 
@@ -359,6 +360,8 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=None,
                     help="time one benchmark configuration 0..4 only (default: configuration 4 as the line, "
                          "configuration 1 in its config1_hbm_regime sub-object)")
+    ap.add_argument("--depth", type=int, default=3,
+                    help="--workload tbody: transformer layers per head (the paper's depth sweep uses 1, 2, 3, 4, 8)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 byte counters)")

@@ -47,7 +47,9 @@ extern "C" {
 typedef struct mrp_ctx mrp_ctx;
 
 /* Problem sizes fixed for the life of a context.
- *   d          hidden size, multiple of 128
+ *   d          hidden size, multiple of 128 and at most 8192 (one k range of the
+ *              GEMM kernels is 128 wide; not the multiple of 8 a plain GEMM
+ *              would accept)
  *   V          vocabulary size, >= 1 (any value; multiples of 4 take the
  *              vectorised logit path)
  *   max_rows   largest M = B * L any call will use
@@ -59,7 +61,12 @@ typedef struct {
 } mrp_dims;
 
 /* One head's weights (device).  W1: [d][2d], W2: [d][d], both packed with
- * mrp_pack_body_weight; gamma: bf16 [d], plain.  Head body (benchmark layout
+ * mrp_pack_body_weight; gamma: bf16 [d], plain.  Every matrix a GEMM kernel
+ * streams (the heads' weights, the transformer layers' projections and the
+ * shared LM head) is taken in the packed layout only: a frozen weight is
+ * packed once at load time (mrp_pack_weight / mrp_pack_body_weight read the
+ * plain row-major bf16 matrix); the embedding table E, which is gathered by
+ * row, stays plain [V][d].  Head body (benchmark layout
  * standing in for the transformer layers of Section 3.2):
  *   x = [h_run ; E[cond_tok]],  a = W1 x,  s = a * sigmoid(a),  u = W2 s,
  *   h_run += u (hidden residual, Algorithm 2 line "h <- h + Delta"),
@@ -71,9 +78,9 @@ typedef struct {
 /* Decision rules of one chain step.
  *   tau          reveal every still-masked row with confidence > tau (strict;
  *                Section 4.1 "Denoising Mode": dynamic denoising)
- *   r_min        forced minimum number of reveals per sequence and state (the
- *                paper's "minimum of one position"); static top-r decoding is
- *                tau >= 1 with r_min = r (Algorithm 2)
+ *   r_min        forced minimum number of reveals per sequence and state
+ *                (dynamic denoising reveals at least one position per step);
+ *                static top-r decoding is tau >= 1 with r_min = r (Algorithm 2)
  *   max_accept   1: cap threshold reveals at min(max(floor(0.7 n), 5), L),
  *                n = masked rows of the sequence (Section 4.4)
  *   carry_hidden 1: h_run <- h_run + u between heads
@@ -95,8 +102,9 @@ typedef struct {
  *                0 the row's top-1 probability under the updated logits (the
  *                definition of confidence, Section 2); 1 the probability the
  *                updated logits give to the token that was revealed at that row
- *                ("the confidence ... stays above tau", Section 3.4, read as a
- *                statement about the revealed token); needs x_tok */
+ *                (Section 3.4's requirement that a reveal keeps its confidence
+ *                over two consecutive steps, read as a statement about the
+ *                revealed token); needs x_tok */
 typedef struct {
     float tau;
     int r_min;
@@ -202,8 +210,8 @@ int mrp_remask(mrp_ctx *ctx, void *stream, int B, int state, const float *conf_n
 int mrp_commit(mrp_ctx *ctx, void *stream, int B, const int32_t *x_tok, int8_t *revealed_at,
                const uint8_t *masked, int32_t *x_out, int32_t *n_masked);
 
-/* Speculative verification (Algorithm 3, "reject drafted positions where the
- * argmaxes differ"): for each sequence b and draft j < K,
+/* Speculative verification (Algorithm 3: a drafted position is rejected where the
+ * verifier's argmax differs from the draft): for each sequence b and draft j < K,
  *   v_j = argmax_v verify[b][draft_pos[b][j]][v],  match[b][j] = (v_j == draft_tok[b][j]);
  *   accept_len[b] = length of the longest all-matching prefix of the K drafts;
  *   correction_tok[b] = v at the first non-matching draft (-1 if all matched or
@@ -277,10 +285,10 @@ int mrp_verify_accept_static(void *stream, int B, int L, int V, int K, const flo
                              uint8_t *match /* [B][K] */, int32_t *accept_len /* [B] */,
                              int32_t *correction_tok /* [B] */);
 
-/* Transformer head body (Section 3.2: the head "fuses [hidden states and token
- * embeddings] via a learned projection, passes the result through a small
- * number of transformer layers, and reuses the backbone's language model
- * head"; D = 3 in Section 4.1).  The layer is the decoder layer of the
+/* Transformer head body (Section 3.2 outlines the head as a learned projection
+ * that fuses the hidden states with the token embeddings, a few transformer
+ * layers, and the backbone's own LM head
+ * on top; D = 3 in Section 4.1).  The layer is the decoder layer of the
  * backbone's model family:
  *   u_0 = W1 [h_run ; E[cond_tok]]                        (the head's W1 is the fuse projection)
  *   n = RMSNorm(u) g1;  q | k | v = Wqkv n;  rotary embedding (rotate-half,
@@ -353,7 +361,9 @@ int mrp_residual_rms(mrp_ctx *ctx, void *stream, int n_blocks, int S, long N, co
 
 /* Timing of the dominant kernel.  With profiling on, every LM-head kernel
  * launched by mrp_chain_step is bracketed by a pair of HIP events on the call's
- * stream (up to 4096 pairs between reads).  mrp_profile_read waits for the
+ * stream (up to 4096 pairs between reads); a chain step recorded while profiling
+ * is on contains event records and is not meant for HIP graph capture: capture
+ * with profiling off (the default).  mrp_profile_read waits for the
  * recorded events, stores up to `cap` elapsed times in milliseconds into the
  * HOST array ms_out, returns how many it stored, and clears the record. */
 int mrp_profile_enable(mrp_ctx *ctx, int on);

@@ -23,7 +23,8 @@
  *       confidence is below the remask threshold (Section 3.4, Algorithm 4).
  *       Variant (remask_mode 1): the confidence compared is the probability
  *       the updated logits assign to the token that was revealed at that
- *       position ("stays above tau" read as a statement about that token),
+ *       position (the requirement that a reveal keeps its confidence over two
+ *       consecutive steps, read as a statement about that token),
  *       not the row's top-1 probability.
  *   - commit: at the end of a denoising step the revealed tokens are written
  *       into the block and those positions stay unmasked in later steps

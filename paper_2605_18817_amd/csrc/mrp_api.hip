@@ -20,8 +20,8 @@ struct mrp_ctx {
     int nT_max;         // partial tiles per row
     size_t part_rows;   // capacity of the k-split partial buffer, in rows of d floats
     int maxB;
-    bool use_tiled;     // 256 x 256 tiled GEMMs for M >= 768 (tuning switch, env MRP_TILED=0 disables)
-    bool lm_persist;    // use the persistent LM-head kernel for M <= 128 (tuning switch, env MRP_LM_PERSIST)
+    bool use_tiled;     // 256 x 256 tiled GEMMs for M >= 768
+    bool lm_persist;    // the persistent LM-head kernel for M <= 128
     int nCU;            // compute units of the device (workgroups of the persistent LM-head kernel)
     char *ws;
     size_t ws_bytes;
@@ -185,12 +185,8 @@ int mrp_create(mrp_ctx **out, const mrp_dims *dims) {
     c->ev_used = 0;
     c->tb_on = false;
     c->tb_ws = nullptr;
-    {   // tuning switch: MRP_LM_PERSIST=0 routes M <= 128 through the generic stream GEMM
-        const char *e = getenv("MRP_LM_PERSIST");
-        c->lm_persist = !(e && e[0] == '0');
-        const char *t = getenv("MRP_TILED");
-        c->use_tiled = !(t && t[0] == '0');
-    }
+    c->lm_persist = true;
+    c->use_tiled = true;
     if (hipGetDevice(&c->device) != hipSuccess ||
         hipDeviceGetAttribute(&c->nCU, hipDeviceAttributeMultiprocessorCount, c->device) != hipSuccess || c->nCU < 1) {
         delete c;

@@ -112,6 +112,14 @@ def test_no_prefix_three_layers_shared_module():
     _run(cfg, td, mrp.RevealCfg(tau=0.9), gain="ones", share=True)
 
 
+@pytest.mark.parametrize("D", [4, 8])
+def test_depth_sweep_four_and_eight_layers(D):
+    """The deeper bodies of the depth sweep (Section 4.5 varies D over 1, 2, 3, 4, 8) on a small case."""
+    cfg = mi.straddling(mi.config(0, B=3, L=4, K=1))
+    td = mi.TBodyDims(D=D, n_heads=2, n_kv_heads=1, head_dim=128, d_ff=256, P_max=70)
+    _run(cfg, td, mrp.RevealCfg(tau=0.9, tau_remask=0.5))
+
+
 def test_many_rows_tiled_gemm_path():
     cfg = mi.config(0, d=512, V=4096, B=48, L=16, K=1)
     td = mi.TBodyDims(D=1, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=512, P_max=64)
