@@ -14,8 +14,9 @@ region.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--skip-cpu-baseline]
 
 Further workloads of the same library, each printing its own JSON line in the same format
-(--workload kl_loss | residual_rms | tbody): the training objective (forward + gradient), the
-residual-magnitude reducer, and the chain with the transformer head body.
+(--workload kl_loss | residual_rms | tbody | lm_traffic): the training objective (forward + gradient), the
+residual-magnitude reducer, the chain with the transformer head body (--depth D), and the bytes of one
+LM-head launch moved without arithmetic (the memory system's floor for that kernel's traffic mix).
 """
 from __future__ import annotations
 
@@ -139,6 +140,51 @@ def bench_residual_rms(args, np, torch, mi, mrp) -> dict:
     return _line("residual-magnitude blocks/s (App. B: 17 states of 16 x V logits) on 1 GPU; % HBM roofline",
                  nb * args.steps / elapsed, "blocks/s", args, elapsed, "f64",
                  f"{nb} blocks x 17 states x {N} fp32 entries (random-walk stand-in states)", roof, cpu)
+
+
+def bench_lm_traffic(args, np, torch, mi, mrp) -> dict:
+    """The bytes of one config-1 LM-head launch (packed W_lm streamed once, the 128 x V logit tile read and
+    written back) moved by mrp_probe_lm_traffic with no arithmetic at all, in three stages, next to the
+    LM-head kernel itself: how much of the kernel's time is the memory system's for this traffic mix."""
+    cfg = mi.CONFIGS[1]
+    d, V, B, L, K, M = cfg.d, cfg.V, cfg.B, cfg.L, cfg.K, cfg.M
+    bits = lambda a: torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).cuda()
+    ctx = mrp.MrpContext(d, V, M, L)
+    Wp_d = mrp.pack_weight(bits(mi.lm_head(cfg)))
+    z_d = torch.from_numpy(mi.logits0(cfg)).cuda()
+    z_before = z_d.clone()
+    wb, zb = 2.0 * V * d, 4.0 * M * V
+    stages = {}
+    for mode, name, byt in ((0, "weights", wb), (1, "weights+z_read", wb + zb), (2, "weights+z_read+z_write", wb + 2 * zb)):
+        _, ev = _time_steps(torch, lambda: ctx.probe_lm_traffic(mode, M, Wp_d, z_d), args.warmup, args.steps)
+        t = ev / args.steps
+        stages[name] = {"us": 1e6 * t, "GBps": byt / t / 1e9, "bytes": byt}
+    assert torch.equal(z_d, z_before), "the probe must leave the logits unchanged"
+    # the kernel itself, in the chain
+    E_d = bits(mi.embedding(cfg))
+    heads_d = [mrp.Head(mrp.pack_weight(bits(w1), body=True), mrp.pack_weight(bits(w2), body=True), bits(g))
+               for (w1, w2, g) in (mi.head_weights(cfg, k) for k in range(K))]
+    h_d = bits(mi.hidden(cfg))
+    hrun_d = torch.zeros((M, d), dtype=torch.float32, device="cuda")
+    io = mrp.StepIO(B, L, K)
+    rcfg = mrp.RevealCfg(tau=cfg.tau, fresh_block=1)
+    step = lambda: ctx.chain_step(B, K, h_d, hrun_d, E_d, Wp_d, heads_d, z_d, rcfg, io)
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    ctx.profile_enable(True)
+    elapsed, _ = _time_steps(torch, step, 0, args.steps)
+    lm_avg = float(np.mean(ctx.profile_read())) * 1e-3
+    ctx.close()
+    full = stages["weights+z_read+z_write"]
+    roof = {"bound": "hbm", "achieved": full["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": full["GBps"] / HBM_PEAK_GBS,
+            "traffic": None, "kernel": "lm_traffic_kernel<2> (no arithmetic)", "kernel_ms": full["us"] * 1e-3,
+            "stages": stages,
+            "lm_persist_kernel_us": 1e6 * lm_avg, "lm_persist_GBps": (wb + 2 * zb) / lm_avg / 1e9,
+            "lm_persist_over_traffic_floor": 1e6 * lm_avg / full["us"]}
+    return _line("bytes of one LM-head launch moved without arithmetic (config 1), GB/s on 1 GPU; % HBM roofline",
+                 full["GBps"], "GB/s", args, full["us"] * 1e-6 * args.steps, "u8",
+                 f"config 1 LM head: {wb / 1e6:.0f} MB packed W_lm + {zb / 1e6:.0f} MB logit tile read and written back", roof, None)
 
 
 def bench_tbody(args, np, torch, mi, mrp) -> dict:
@@ -291,12 +337,12 @@ def run_chain_config(cfg, args, np, torch, mi, mrp) -> dict:
         ach = lm_flops / (lm_avg_ms * 1e-3) / 1e12
         roof = {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                 "frac": ach / MFMA_BF16_PEAK_TFLOPS}
-    roof["traffic"] = traffic_from_profile(cfg.cid)
+    roof["traffic"] = traffic_from_profile(cfg.cid) if cfg == mi.CONFIGS[cfg.cid] else None
     roof["traffic_source"] = (f"profiles/lm_head_cfg{cfg.cid}_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier "
                               "run of this command, scaled by what the counters read for a 1 GiB copy; not measured in this run"
                               if roof["traffic"] is not None else None)
     roof["kernel"] = ("lm_persist_kernel" if M <= 128 and V % 4 == 0 else
-                      "tiled_gemm_kernel<EPI_LM>" if M >= 768 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
+                      "tiled_gemm_kernel<EPI_LM>" if M >= 448 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
     roof["kernel_ms"] = lm_avg_ms
     roof["launches"] = len(lm_ms)
     roof["algorithmic_bytes_per_launch"] = lm_bytes
@@ -352,7 +398,7 @@ def chain_line(res: dict, args) -> dict:
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody"],
+    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody", "lm_traffic"],
                     help="chain (default): the headline metric; the others time further entry points")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
@@ -360,6 +406,9 @@ def main() -> int:
     ap.add_argument("--config", type=int, default=None,
                     help="time one benchmark configuration 0..4 only (default: configuration 4 as the line, "
                          "configuration 1 in its config1_hbm_regime sub-object)")
+    ap.add_argument("--batch", type=int, default=None,
+                    help="with --config N: override the number of sequences B (e.g. --config 2 --batch 32 times the "
+                         "512-row case that runs on the streaming kernel between the persistent and the tiled one)")
     ap.add_argument("--depth", type=int, default=3,
                     help="--workload tbody: transformer layers per head (the paper's depth sweep uses 1, 2, 3, 4, 8)")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
@@ -382,12 +431,14 @@ def main() -> int:
         return 3
 
     if args.workload != "chain":
-        fn = {"kl_loss": bench_kl_loss, "residual_rms": bench_residual_rms, "tbody": bench_tbody}[args.workload]
+        fn = {"kl_loss": bench_kl_loss, "residual_rms": bench_residual_rms, "tbody": bench_tbody,
+              "lm_traffic": bench_lm_traffic}[args.workload]
         print(json.dumps(fn(args, np, torch, mi, mrp)))
         return 0
 
     if args.config is not None:
-        res = run_chain_config(mi.CONFIGS[args.config], args, np, torch, mi, mrp)
+        cfg = mi.CONFIGS[args.config] if args.batch is None else mi.config(args.config, B=args.batch)
+        res = run_chain_config(cfg, args, np, torch, mi, mrp)
         print(json.dumps(chain_line(res, args)))
         return 0
     # default: the largest configuration (MFMA-bound) is the line; the SDAR-1.7B-shaped configuration

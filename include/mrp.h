@@ -369,6 +369,15 @@ int mrp_residual_rms(mrp_ctx *ctx, void *stream, int n_blocks, int S, long N, co
 int mrp_profile_enable(mrp_ctx *ctx, int on);
 int mrp_profile_read(mrp_ctx *ctx, float *ms_out, int cap);
 
+/* Measurement aid (not part of the method): move the bytes of one LM-head launch at M <= 128 rows
+ * with the persistent LM-head kernel's work split and access pattern and none of its arithmetic.
+ *   mode 0  stream the packed W_lm once
+ *   mode 1  ... and read the [M][V] logit tile
+ *   mode 2  ... and write the logit tile back (the same values: z is unchanged)
+ * Its time is the floor the memory system sets for that traffic mix; bench.py --workload lm_traffic
+ * reports it next to the kernel.  Needs V % 4 == 0 and d % 256 == 0. */
+int mrp_probe_lm_traffic(mrp_ctx *ctx, void *stream, int mode, int M, const void *W_lm_packed, float *z);
+
 #ifdef __cplusplus
 }
 #endif

@@ -12,7 +12,7 @@ EXPORTED_SYMBOLS = [
     "mrp_create", "mrp_destroy", "mrp_workspace_bytes", "mrp_last_error", "mrp_packed_bytes",
     "mrp_pack_weight", "mrp_pack_body_weight", "mrp_chain_step", "mrp_remask", "mrp_commit", "mrp_verify_accept", "mrp_verify_accept_joint", "mrp_kl_loss", "mrp_residual_rms", "mrp_tbody_create", "mrp_chain_step_tf",
     "mrp_profile_enable", "mrp_profile_read", "mrp_verify_accept_static", "mrp_verify_accept_static_scratch_bytes",
-    "mrp_build_candidates", "mrp_poll_error",
+    "mrp_build_candidates", "mrp_poll_error", "mrp_probe_lm_traffic",
 ]
 
 MRP_MAX_HEADS = 16
@@ -104,6 +104,7 @@ def load_library():
     lib.mrp_build_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p,
                                          C.c_void_p, C.c_int, C.c_int32, C.c_void_p, C.c_void_p]
     lib.mrp_poll_error.argtypes = [C.c_void_p, C.c_void_p]
+    lib.mrp_probe_lm_traffic.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
     lib.mrp_profile_enable.argtypes = [C.c_void_p, C.c_int]
     lib.mrp_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), C.c_int]
     _lib = lib
@@ -342,6 +343,10 @@ class MrpContext:
                                            _ptr(draft_tok), draft_stride, mask_token, _ptr(cand_tok),
                                            _ptr(cand_masked))
         return self._check(rc, "mrp_build_candidates") if check else rc
+
+    def probe_lm_traffic(self, mode: int, M: int, W_lm_packed, z, check: bool = True) -> int:
+        rc = self.lib.mrp_probe_lm_traffic(self._h, _stream(), mode, M, _ptr(W_lm_packed), _ptr(z))
+        return self._check(rc, "mrp_probe_lm_traffic") if check else rc
 
     def poll_error(self) -> int:
         """Wait for the current stream; bits of the device error word set since the last poll (cleared)."""

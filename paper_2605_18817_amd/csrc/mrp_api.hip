@@ -443,8 +443,12 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
     for (int k = 1; k <= K; ++k) {
         const mrp_head &hd = heads[k - 1];
         StreamGemmArgs g;
-        // 256 x 256 tiles pay off once there are enough of them to fill the chip more than once
+        // 256 x 256 tiles pay off once there are enough of them to fill the chip more than once: from 768
+        // rows for the head body's GEMMs.  The LM head has V / 256 tiles per 256 rows, and its tile
+        // kernel overtakes the streaming kernel between 256 and 512 rows (measured at d = 4096,
+        // V = 151936: 930 / 952 / 1031 us at 256 / 512 / 752 rows against 590 / 1079 / 1500 us)
         const bool tiled = c->use_tiled && M >= 768;
+        const bool tiled_lm = c->use_tiled && M >= 448;
         int nks1 = 1, nks2 = 1;
         // a = W1 [h_run ; e]
         if (tiled) {
@@ -559,7 +563,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             HIP_TRY(c, launch_lm_persist(la, st));
             nT_lm = la.nWG;
             lm_rowmajor = true;
-        } else if (tiled && V % 4 == 0) {
+        } else if (tiled_lm && V % 4 == 0) {
             TiledGemmArgs tg;
             memset(&tg, 0, sizeof(tg));
             tg.Wp = static_cast<const uint4 *>(W_lm_packed);
@@ -699,6 +703,18 @@ int mrp_poll_error(mrp_ctx *c, void *stream) {
                  (flags & MRP_FLAG_X_TOK) ? " recorded token >= V (clamped)" : "");
     }
     return flags;
+}
+
+int mrp_probe_lm_traffic(mrp_ctx *c, void *stream, int mode, int M, const void *W_lm_packed, float *z) {
+    if (!c) return MRP_ERR_NULL;
+    if (!W_lm_packed || (mode >= 1 && !z)) return fail(c, MRP_ERR_NULL, "mrp_probe_lm_traffic: NULL pointer");
+    if (mode < 0 || mode > 2 || M < 1 || M > 128 || M > c->dims.max_rows || c->dims.V % 4 != 0 || c->dims.d % 256 != 0)
+        return fail(c, MRP_ERR_SHAPE, "mrp_probe_lm_traffic: mode 0..2, 1 <= M <= 128, V %% 4 == 0, d %% 256 == 0");
+    if (!aligned16(W_lm_packed) || (z && !aligned16(z))) return fail(c, MRP_ERR_ALIGN, "mrp_probe_lm_traffic: 16-byte alignment");
+    HIP_TRY(c, launch_lm_traffic(mode, static_cast<const uint4 *>(W_lm_packed), z, c->dims.d / 16, (c->dims.V + 31) / 32, M,
+                                 c->dims.V, c->nCU, reinterpret_cast<unsigned *>(c->err_flag + 8),
+                                 static_cast<hipStream_t>(stream)));
+    return MRP_OK;
 }
 
 }  // extern "C"

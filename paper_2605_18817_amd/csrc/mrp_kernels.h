@@ -298,6 +298,9 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
                             const uint16_t *kc, const uint16_t *vc, const int32_t *prefix_len, int P_max,
                             uint4 *o_planes, long plane_stride, int nIb, hipStream_t st);
 
+hipError_t launch_lm_traffic(int mode, const uint4 *Wp, float *z, int KB, int n_rb, int M, int V, int nWG,
+                             unsigned *sink, hipStream_t st);
+
 size_t residual_rms_part_bytes();
 int residual_rms_max_blocks();
 bool residual_rms_supported(int S);

@@ -173,6 +173,22 @@ def test_config2_full_batch():
         prob.close()
 
 
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("B", [24, 32])
+def test_config2_middle_row_range(B):
+    """Between the persistent LM-head kernel (at most 128 rows) and the all-tiled path (768 rows and
+    more): at 384 rows (B = 24) the LM head and the head GEMMs run on the streaming kernel with 256-row
+    workgroups, at 512 rows (B = 32) the LM head runs on the tiled kernel and the head GEMMs on the
+    streaming one.  One sequence from every 256-row group."""
+    cfg = mi.config(2, B=B)
+    assert 128 < cfg.M < 768
+    prob, io, g, stats = _run_full(cfg, mrp.RevealCfg(tau=cfg.tau), seqs=one_sequence_per_row_tile(cfg))
+    try:
+        _run_teacher_forced(prob, cfg, mrp.RevealCfg(tau=cfg.tau), seqs=one_sequence_per_row_tile(cfg, salt=1))
+    finally:
+        prob.close()
+
+
 @pytest.mark.timeout(1100)
 def test_config3_draft_then_verify():
     cfg = mi.config(3)
