@@ -405,6 +405,14 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
     const int IT = stream_gemm_it(M);
     const int nMg = ((M + 31) / 32 + IT - 1) / IT;
     const int off = cfg->state_offset;
+    // MLP body below the 256 x 256 tile kernel's range: GEMMs that reduce their k split inside the workgroup
+    // (no partial sums in memory) and read the conditioning embeddings from the table themselves (no gathered
+    // copy is made).  The streaming kernel with its partial sums stays ahead only for wide models whose row
+    // count fills its 256-row groups (measured at d = 4096: 150 / 205 us per head at 256 / 512 rows against
+    // 154 / 251 us, but 271 / 385 us at 384 / 640 rows against 206 / 336 us; at d = 2048 it is behind
+    // everywhere: 102 / 133 / 160 us at 256 / 512 / 640 rows against 76 / 105 / 128 us).
+    const int last_group_empty = (M + 255) / 256 * 256 - M;
+    const bool fused = !layers && d % 128 == 0 && M < 768 && (M <= 128 || d <= 2048 || last_group_empty >= 64);
 
     SelectArgs sa;
     memset(&sa, 0, sizeof(sa));
@@ -428,9 +436,9 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         sa.tok = io->tok; sa.conf = io->conf; sa.lse = io->lse;
         sa.draft_pos = io->draft_pos; sa.draft_tok = io->draft_tok;
         sa.remasked = io->remasked;
-        sa.E = K > 0 ? Eb : nullptr;
+        sa.E = (K > 0 && !fused) ? Eb : nullptr;
         HIP_TRY(c, launch_merge_select(sa, st));
-    } else if (K > 0) {
+    } else if (K > 0 && !fused) {
         HIP_TRY(c, launch_gather_e(Eb, io->cond_tok, c->XE, c->nIb, B, L, d, V, c->err_flag, st));
     }
     if (K == 0) return MRP_OK;
@@ -450,6 +458,21 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         const bool tiled = c->use_tiled && M >= 768;
         const bool tiled_lm = c->use_tiled && M >= 448;
         int nks1 = 1, nks2 = 1;
+        const float *resid = nullptr;   // transformer body: residual stream added to the last projection
+        if (fused) {
+            // s = SiLU(W1 [h ; e]) with e read from the embedding table, then u = W2 s
+            HeadFusedArgs fa;
+            memset(&fa, 0, sizeof(fa));
+            fa.W1p = static_cast<const uint4 *>(hd.W1_packed);
+            fa.W2p = static_cast<const uint4 *>(hd.W2_packed);
+            fa.XH = c->XH; fa.plane = c->plane; fa.np_h = np_h;
+            fa.E = Eb; fa.cond_tok = io->cond_tok; fa.L = L; fa.V = V;
+            fa.S = c->S; fa.U = c->PART;
+            fa.nIb = c->nIb; fa.M = M; fa.d = d;
+            fa.err_flag = c->err_flag;
+            fa.nct = d / 32; fa.nrt = (M + 31) / 32;
+            HIP_TRY(c, launch_head_fused(fa, st));
+        } else {
         // a = W1 [h_run ; e]
         if (tiled) {
             TiledGemmArgs tg;
@@ -475,7 +498,6 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             nks1 = g.nKs;
             HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
         }
-        const float *resid = nullptr;   // transformer body: residual stream added to the last projection
         if (layers) {
             const mrp_tbody_dims &tb = c->tb;
             const int qd = tb.n_heads * tb.head_dim, qkvd = qd + 2 * tb.n_kv_heads * tb.head_dim, ff = tb.d_ff;
@@ -539,6 +561,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             HIP_TRY(c, launch_stream_gemm(g, EPI_PARTIAL, st));
         }
         }
+        }
         // h_run += u ; y = bf16(RMSNorm(u) * gamma)
         HIP_TRY(c, launch_norm(c->PART, nks2, resid, static_cast<const uint16_t *>(hd.gamma), c->dims.rms_eps, h_run,
                                cfg->carry_hidden != 0, c->Y, c->XH, c->plane, c->nIb, M, d, st));
@@ -598,7 +621,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         sa.tok = io->tok + (size_t)k * M; sa.conf = io->conf + (size_t)k * M; sa.lse = io->lse + (size_t)k * M;
         sa.draft_pos = io->draft_pos + k; sa.draft_tok = io->draft_tok + k;
         sa.remasked = io->remasked ? io->remasked + (size_t)k * M : nullptr;
-        sa.E = k < K ? Eb : nullptr;
+        sa.E = (k < K && !fused) ? Eb : nullptr;
         HIP_TRY(c, launch_merge_select(sa, st));
     }
     return MRP_OK;
@@ -696,7 +719,7 @@ int mrp_poll_error(mrp_ctx *c, void *stream) {
     HIP_TRY(c, hipMemcpy(&flags, c->err_flag, sizeof(int), hipMemcpyDeviceToHost));
     if (flags) {
         HIP_TRY(c, hipMemset(c->err_flag, 0, sizeof(int)));
-        snprintf(c->err, sizeof(c->err), "device error word 0x%x:%s%s%s%s", flags,
+        snprintf(c->err, sizeof(c->err), "device error word 0x%x:%s%s%s%s", (unsigned)flags,
                  (flags & MRP_FLAG_COND_TOK) ? " cond_tok out of range (clamped)" : "",
                  (flags & MRP_FLAG_DRAFT_POS) ? " draft position >= block length (taken as missing)" : "",
                  (flags & MRP_FLAG_PREFIX_LEN) ? " prefix_len outside [0, max_prefix] (clamped)" : "",

@@ -92,6 +92,23 @@ struct TiledGemmArgs {
 // passed in device memory was out of range; the kernel clamped or skipped it and reports it here.
 enum { ERR_COND_TOK = 1, ERR_DRAFT_POS = 2, ERR_PREFIX_LEN = 4, ERR_X_TOK = 8 };
 
+// MLP head body for fewer than 768 activation rows without partial sums in memory (head_fused.hip)
+struct HeadFusedArgs {
+    const uint4 *W1p;          // packed fp16 W1 [d / 32][2 d / 16][64]
+    const uint4 *W2p;          // packed fp16 W2 [d / 32][d / 16][64]
+    const uint4 *XH;           // planes of the running hidden state
+    long plane;                // plane stride (uint4 units) of XH and S
+    int np_h;                  // planes of XH to read (1: the state is an exact single term)
+    const uint16_t *E;         // embedding table [V][d] bf16
+    const int32_t *cond_tok;   // [B] conditioning token per sequence
+    int L, V;
+    uint4 *S;                  // planes of s = SiLU(a): written by the first launch, read by the second
+    float *U;                  // [M][d] fp32 u = W2 s
+    int nIb, M, d;
+    int *err_flag;
+    int nct, nrt;              // feature tiles d / 32, row tiles ceil(M / 32)
+};
+
 // row-reduction partial: running max, sum of exp(x - max), index of the max
 struct Part {
     float m, s;
@@ -297,6 +314,8 @@ hipError_t launch_swiglu_split(const float *part, int nKs, uint4 *planes, long p
 hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int nh, int nkv, const float2 *rope,
                             const uint16_t *kc, const uint16_t *vc, const int32_t *prefix_len, int P_max,
                             uint4 *o_planes, long plane_stride, int nIb, hipStream_t st);
+
+hipError_t launch_head_fused(const HeadFusedArgs &a, hipStream_t st);   // both GEMMs: S and U written
 
 hipError_t launch_lm_traffic(int mode, const uint4 *Wp, float *z, int KB, int n_rb, int M, int V, int nWG,
                              unsigned *sink, hipStream_t st);
