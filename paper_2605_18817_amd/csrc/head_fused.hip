@@ -3,6 +3,8 @@
 // partial sums in memory: each GEMM reduces its k split inside the workgroup
 // through LDS, the first reads the conditioning embedding straight from the
 // embedding table and applies the SiLU in its epilogue, the second writes u.
+// The second kernel is a plain small-row GEMM and also serves the projections
+// of the transformer head body (Section 4.5).
 //
 // A workgroup of 8 wavefronts owns one 32 x 32 output tile (32 activation rows
 // x 32 features); wave w takes the 16-wide k blocks kb = w, w + 8, ... of the
@@ -118,12 +120,12 @@ __device__ __forceinline__ void wave_gemm_embed(f32x16 &acc, const u32x4 *wrow, 
 
 // workgroup -> tile: consecutive ids go to different XCDs (8, each with its own L2); the row tiles of
 // one feature tile share its weight rows, so they sit on one XCD
-__device__ __forceinline__ bool tile_of(const HeadFusedArgs &a, int &rt, int &ct) {
-    const int nWG = a.nct * a.nrt;
+__device__ __forceinline__ bool tile_of(int nct, int nrt, int &rt, int &ct) {
+    const int nWG = nct * nrt;
     const int per = (nWG + 7) >> 3;
     const int w_id = (blockIdx.x & 7) * per + (blockIdx.x >> 3);
-    rt = w_id % a.nrt;
-    ct = w_id / a.nrt;
+    rt = w_id % nrt;
+    ct = w_id / nrt;
     return w_id < nWG;
 }
 
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(HF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ln = lane & 31, lh = lane >> 5;
     int rt, ct;
-    if (!tile_of(a, rt, ct)) return;
+    if (!tile_of(a.nct, a.nrt, rt, ct)) return;
     const int KBd = a.d >> 4;          // k blocks per d columns
     const int nj = KBd / HF_WAVES;     // k blocks per wave per d columns (d % 128 == 0)
     const size_t kstride = (size_t)a.nIb * 64;
@@ -171,25 +173,27 @@ __global__ __launch_bounds__(HF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4
     }
 }
 
-// u = W2 s, fp32 [M][d]
-__global__ __launch_bounds__(HF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void head_gemm2_kernel(
-    const HeadFusedArgs a) {
+// out [M][R] fp32 = X W^T for packed fp16 weights [R / 32][Kc / 16][64] and an activation of one or two
+// fp16 planes (the head's second GEMM u = W2 s, and the projections of the transformer body)
+__global__ __launch_bounds__(HF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4))) void small_gemm_kernel(
+    const SmallGemmArgs a) {
     __shared__ float tile[HF_WAVES][32][HF_LD];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ln = lane & 31, lh = lane >> 5;
     int rt, ct;
-    if (!tile_of(a, rt, ct)) return;
-    const int KBd = a.d >> 4;
-    const int nj = KBd / HF_WAVES;
+    if (!tile_of(a.nct, a.nrt, rt, ct)) return;
+    const int KB = a.Kc >> 4;
+    const int nj = KB / HF_WAVES;   // (Kc % 128 == 0)
     const size_t kstride = (size_t)a.nIb * 64;
     {
         f32x16 acc;
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-        const u32x4 *wrow = reinterpret_cast<const u32x4 *>(a.W2p) + (size_t)ct * KBd * 64 + lane;
-        const u32x4 *xs = reinterpret_cast<const u32x4 *>(a.S) + (size_t)rt * 64 + lane;
-        wave_gemm_planes<2>(acc, wrow, 0, xs, a.plane, kstride, nj, wave);
+        const u32x4 *wrow = reinterpret_cast<const u32x4 *>(a.Wp) + (size_t)ct * KB * 64 + lane;
+        const u32x4 *xs = reinterpret_cast<const u32x4 *>(a.X) + (size_t)rt * 64 + lane;
+        if (a.nplanes == 2) wave_gemm_planes<2>(acc, wrow, 0, xs, a.plane, kstride, nj, wave);
+        else wave_gemm_planes<1>(acc, wrow, 0, xs, a.plane, kstride, nj, wave);
         spill_tile(tile[wave], acc, ln, lh);
     }
     __syncthreads();
@@ -199,7 +203,7 @@ __global__ __launch_bounds__(HF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4
         float u[8];
         reduce_chunk(tile, row, c, u);
         if (i < a.M) {
-            float4 *up = reinterpret_cast<float4 *>(a.U + (size_t)i * a.d + 32 * ct + 8 * c);
+            float4 *up = reinterpret_cast<float4 *>(a.out + (size_t)i * a.R + 32 * ct + 8 * c);
             up[0] = make_float4(u[0], u[1], u[2], u[3]);
             up[1] = make_float4(u[4], u[5], u[6], u[7]);
         }
@@ -208,12 +212,21 @@ __global__ __launch_bounds__(HF_THREADS) __attribute__((amdgpu_waves_per_eu(4, 4
 
 }  // namespace
 
-hipError_t launch_head_fused(const HeadFusedArgs &a, hipStream_t st) {
-    const int nWG = a.nct * a.nrt;
-    const int per = (nWG + 7) / 8;
-    hipLaunchKernelGGL(head_gemm1_kernel, dim3(per * 8), dim3(HF_THREADS), 0, st, a);
-    hipLaunchKernelGGL(head_gemm2_kernel, dim3(per * 8), dim3(HF_THREADS), 0, st, a);
+hipError_t launch_small_gemm(const SmallGemmArgs &a, hipStream_t st) {
+    const int per = (a.nct * a.nrt + 7) / 8;
+    hipLaunchKernelGGL(small_gemm_kernel, dim3(per * 8), dim3(HF_THREADS), 0, st, a);
     return hipGetLastError();
+}
+
+hipError_t launch_head_fused(const HeadFusedArgs &a, hipStream_t st) {
+    const int per = (a.nct * a.nrt + 7) / 8;
+    hipLaunchKernelGGL(head_gemm1_kernel, dim3(per * 8), dim3(HF_THREADS), 0, st, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    SmallGemmArgs g;
+    g.Wp = a.W2p; g.X = a.S; g.plane = a.plane; g.nplanes = NSPLIT; g.out = a.U;
+    g.nIb = a.nIb; g.M = a.M; g.R = a.d; g.Kc = a.d; g.nct = a.nct; g.nrt = a.nrt;
+    return launch_small_gemm(g, st);
 }
 
 }  // namespace mrp

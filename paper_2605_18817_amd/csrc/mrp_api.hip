@@ -133,6 +133,16 @@ int pick_ksplit(int nVt, int nMg, int G, size_t part_rows, int M) {
     return want < 1 ? 1 : want;
 }
 
+// Below the 256 x 256 tile kernel's range: the GEMM kernels that reduce their k split inside the workgroup
+// (no partial sums in memory).  The streaming kernel with its partial sums stays ahead only for wide
+// operands whose row count fills its 256-row groups (measured on the MLP body at d = 4096: 150 / 205 us per
+// head at 256 / 512 rows against 154 / 251 us, but 271 / 385 us at 384 / 640 rows against 206 / 336 us; at
+// d = 2048 it is behind everywhere: 102 / 133 / 160 us at 256 / 512 / 640 rows against 76 / 105 / 128 us).
+bool small_rows_kernel(int M, int Kc) {
+    const int last_group_empty = (M + 255) / 256 * 256 - M;
+    return M < 768 && (M <= 128 || Kc <= 2048 || last_group_empty >= 64);
+}
+
 // out[ks][M][R] = partial sums of W [R][Kc] (packed) times the activation planes; returns the number
 // of k splits written (1 for the tiled kernel) or -1 after a launch error (*err set).
 int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, const uint4 *act, long plane_stride,
@@ -147,6 +157,14 @@ int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, cons
         tg.nMt = (M + 255) / 256; tg.nVt = R / 256;
         tg.out = out;
         *err = launch_tiled_gemm(tg, EPI_PARTIAL, st);
+        return *err == hipSuccess ? 1 : -1;
+    }
+    if (small_rows_kernel(M, Kc) && R % 32 == 0 && Kc % 128 == 0 && nplanes <= 2) {
+        SmallGemmArgs sg;
+        sg.Wp = static_cast<const uint4 *>(Wp); sg.X = act; sg.plane = plane_stride; sg.nplanes = nplanes;
+        sg.out = out; sg.nIb = c->nIb; sg.M = M; sg.R = R; sg.Kc = Kc;
+        sg.nct = R / 32; sg.nrt = (M + 31) / 32;
+        *err = launch_small_gemm(sg, st);
         return *err == hipSuccess ? 1 : -1;
     }
     const int IT = stream_gemm_it(M);
@@ -405,14 +423,9 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
     const int IT = stream_gemm_it(M);
     const int nMg = ((M + 31) / 32 + IT - 1) / IT;
     const int off = cfg->state_offset;
-    // MLP body below the 256 x 256 tile kernel's range: GEMMs that reduce their k split inside the workgroup
-    // (no partial sums in memory) and read the conditioning embeddings from the table themselves (no gathered
-    // copy is made).  The streaming kernel with its partial sums stays ahead only for wide models whose row
-    // count fills its 256-row groups (measured at d = 4096: 150 / 205 us per head at 256 / 512 rows against
-    // 154 / 251 us, but 271 / 385 us at 384 / 640 rows against 206 / 336 us; at d = 2048 it is behind
-    // everywhere: 102 / 133 / 160 us at 256 / 512 / 640 rows against 76 / 105 / 128 us).
-    const int last_group_empty = (M + 255) / 256 * 256 - M;
-    const bool fused = !layers && d % 128 == 0 && M < 768 && (M <= 128 || d <= 2048 || last_group_empty >= 64);
+    // MLP body at small row counts: the first GEMM also reads the conditioning embeddings from the table
+    // itself (no gathered copy is made) and applies the SiLU
+    const bool fused = !layers && d % 128 == 0 && small_rows_kernel(M, d);
 
     SelectArgs sa;
     memset(&sa, 0, sizeof(sa));

@@ -315,6 +315,17 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
                             const uint16_t *kc, const uint16_t *vc, const int32_t *prefix_len, int P_max,
                             uint4 *o_planes, long plane_stride, int nIb, hipStream_t st);
 
+// out [M][R] fp32 = X W^T, k split reduced inside the workgroup (R % 32 == 0, Kc % 128 == 0)
+struct SmallGemmArgs {
+    const uint4 *Wp;           // packed fp16 weights [R / 32][Kc / 16][64]
+    const uint4 *X;            // activation planes [Kc / 16][nIb][64]
+    long plane;                // plane stride (uint4 units)
+    int nplanes;               // 1 or 2
+    float *out;                // [M][R]
+    int nIb, M, R, Kc;
+    int nct, nrt;              // feature tiles R / 32, row tiles ceil(M / 32)
+};
+hipError_t launch_small_gemm(const SmallGemmArgs &a, hipStream_t st);
 hipError_t launch_head_fused(const HeadFusedArgs &a, hipStream_t st);   // both GEMMs: S and U written
 
 hipError_t launch_lm_traffic(int mode, const uint4 *Wp, float *z, int KB, int n_rb, int M, int V, int nWG,
