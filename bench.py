@@ -342,7 +342,7 @@ def run_chain_config(cfg, args, np, torch, mi, mrp) -> dict:
                               "run of this command, scaled by what the counters read for a 1 GiB copy; not measured in this run"
                               if roof["traffic"] is not None else None)
     roof["kernel"] = ("lm_persist_kernel" if M <= 128 and V % 4 == 0 else
-                      "tiled_gemm_kernel<EPI_LM>" if M >= 448 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
+                      "tiled_gemm_kernel<EPI_LM>" if M > 256 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
     roof["kernel_ms"] = lm_avg_ms
     roof["launches"] = len(lm_ms)
     roof["algorithmic_bytes_per_launch"] = lm_bytes

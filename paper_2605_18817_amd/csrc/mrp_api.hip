@@ -465,11 +465,12 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         const mrp_head &hd = heads[k - 1];
         StreamGemmArgs g;
         // 256 x 256 tiles pay off once there are enough of them to fill the chip more than once: from 768
-        // rows for the head body's GEMMs.  The LM head has V / 256 tiles per 256 rows, and its tile
-        // kernel overtakes the streaming kernel between 256 and 512 rows (measured at d = 4096,
-        // V = 151936: 930 / 952 / 1031 us at 256 / 512 / 752 rows against 590 / 1079 / 1500 us)
+        // rows for the head body's GEMMs.  The LM head has V / 256 tiles per 256 rows; the streaming kernel
+        // takes the rows in groups of 256 and its time doubles with a second group, so the tile kernel is
+        // ahead from 257 rows on (measured at d = 4096, V = 151936: 930 / 952 / 1031 us at 256 / 512 / 752
+        // rows against 590 us at 256 and 1050 us at 384 rows)
         const bool tiled = c->use_tiled && M >= 768;
-        const bool tiled_lm = c->use_tiled && M >= 448;
+        const bool tiled_lm = c->use_tiled && M > 256;
         int nks1 = 1, nks2 = 1;
         const float *resid = nullptr;   // transformer body: residual stream added to the last projection
         if (fused) {
