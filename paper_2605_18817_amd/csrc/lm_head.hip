@@ -28,18 +28,21 @@ __device__ __forceinline__ bf16x8 as_frag(const u32x4 &u) { return __builtin_bit
 
 constexpr int LM_WAVES = 8;
 constexpr int LM_THREADS = 64 * LM_WAVES;
-constexpr int LM_IT = 4;                       // 4 x 32 activation rows
-constexpr int LM_ROWS = 32 * LM_IT;
-constexpr int LM_STAGE = KSTEP * LM_IT * 64;   // u32x4 per activation stage (32 KiB)
-constexpr int LM_NLD = LM_STAGE / LM_THREADS;  // u32x4 per thread per stage
+constexpr int LM_IT_MAX = 4;                   // up to 4 x 32 activation rows
 #ifndef MRP_LM_RING
 #define MRP_LM_RING 3
 #endif
 constexpr int LM_RING = MRP_LM_RING;           // k ranges of weight fragments held per wave (2 or 3)
 static_assert(LM_RING == 2 || LM_RING == 3, "ring depth");
 
-__global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel(
-    const LmPersistArgs a) {
+// LM_IT: 32-row blocks of activation rows that are computed (1, 2 or 4: a launch with at most 32 or 64 rows
+// skips the matrix-core and LDS work of the empty blocks, which the 128-row form only just hides behind its
+// memory time)
+template <int LM_IT>
+__device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
+    constexpr int LM_ROWS = 32 * LM_IT;
+    constexpr int LM_STAGE = KSTEP * LM_IT * 64;   // u32x4 per activation stage (32 KiB at 4 blocks)
+    constexpr int LM_NLD = LM_STAGE / LM_THREADS;  // u32x4 per thread per stage
     extern __shared__ u32x4 smem[];
     // reduction scratch, one copy per pass parity (a pass may end one iteration after the last)
     float *red_base = reinterpret_cast<float *>(smem + 2 * LM_STAGE);
@@ -259,18 +262,40 @@ __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
 #undef LM_YLOAD
 }
 
+__global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel(
+    const LmPersistArgs a) {
+    lm_persist_body<4>(a);
+}
+__global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel_64rows(
+    const LmPersistArgs a) {
+    lm_persist_body<2>(a);
+}
+__global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel_32rows(
+    const LmPersistArgs a) {
+    lm_persist_body<1>(a);
+}
+
 }  // namespace
 
-size_t lm_persist_lds_bytes() { return (size_t)2 * LM_STAGE * 16 + (size_t)2 * LM_WAVES * LM_ROWS * 12; }
+// (sized for the 128-row form; the smaller forms use less)
+size_t lm_persist_lds_bytes() {
+    return (size_t)2 * KSTEP * LM_IT_MAX * 64 * 16 + (size_t)2 * LM_WAVES * 32 * LM_IT_MAX * 12;
+}
 
-// Once per device (mrp_create): the kernel needs more than the default 64 KiB of dynamic LDS.
+// Once per device (mrp_create): the kernels need more than the default 64 KiB of dynamic LDS.
 hipError_t lm_persist_configure() {
-    return hipFuncSetAttribute(reinterpret_cast<const void *>(lm_persist_kernel),
-                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lm_persist_lds_bytes());
+    hipError_t e = hipSuccess;
+    for (const void *k : {reinterpret_cast<const void *>(lm_persist_kernel),
+                          reinterpret_cast<const void *>(lm_persist_kernel_64rows),
+                          reinterpret_cast<const void *>(lm_persist_kernel_32rows)})
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(k, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lm_persist_lds_bytes());
+    return e;
 }
 
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st) {
-    hipLaunchKernelGGL(lm_persist_kernel, dim3(a.nWG), dim3(LM_THREADS), lm_persist_lds_bytes(), st, a);
+    auto k = a.M <= 32 ? lm_persist_kernel_32rows : (a.M <= 64 ? lm_persist_kernel_64rows : lm_persist_kernel);
+    hipLaunchKernelGGL(k, dim3(a.nWG), dim3(LM_THREADS), lm_persist_lds_bytes(), st, a);
     return hipGetLastError();
 }
 
