@@ -14,9 +14,10 @@ region.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config N] [--skip-cpu-baseline]
 
 Further workloads of the same library, each printing its own JSON line in the same format
-(--workload kl_loss | residual_rms | tbody | lm_traffic): the training objective (forward + gradient), the
-residual-magnitude reducer, the chain with the transformer head body (--depth D), and the bytes of one
-LM-head launch moved without arithmetic (the memory system's floor for that kernel's traffic mix).
+(--workload kl_loss | residual_rms | tbody | lm_traffic | library_gemm): the training objective (forward +
+gradient), the residual-magnitude reducer, the chain with the transformer head body (--depth D), the bytes of
+one LM-head launch moved without arithmetic (the memory system's floor for that kernel's traffic mix), and, as
+context only, the vendor library's plain GEMM on the LM head's contraction.
 """
 from __future__ import annotations
 
@@ -185,6 +186,30 @@ def bench_lm_traffic(args, np, torch, mi, mrp) -> dict:
     return _line("bytes of one LM-head launch moved without arithmetic (config 1), GB/s on 1 GPU; % HBM roofline",
                  full["GBps"], "GB/s", args, full["us"] * 1e-6 * args.steps, "u8",
                  f"config 1 LM head: {wb / 1e6:.0f} MB packed W_lm + {zb / 1e6:.0f} MB logit tile read and written back", roof, None)
+
+
+def bench_library_gemm(args, np, torch, mi, mrp) -> dict:
+    """Context only, no part of the path: the vendor library's plain bf16 GEMM (torch.matmul, bf16 output) on the
+    LM head's contraction y W_lm^T at configs 2, 3, 4's row counts -- no logit state, no residual add, no
+    vocabulary reduction -- next to which the fused LM-head tile kernel can be read."""
+    d, V = mi.CONFIGS[4].d, mi.CONFIGS[4].V
+    g = torch.Generator(device="cuda"); g.manual_seed(1)
+    W = (torch.randn(V, d, device="cuda", generator=g) * 0.02).to(torch.bfloat16)
+    rows = {}
+    for M in (1024, 2048, 4096):
+        y = torch.randn(M, d, device="cuda", generator=g).to(torch.bfloat16)
+        out = torch.empty(M, V, device="cuda", dtype=torch.bfloat16)
+        _, ev = _time_steps(torch, lambda: torch.matmul(y, W.t(), out=out), args.warmup, args.steps)
+        t = ev / args.steps
+        rows[str(M)] = {"us": 1e6 * t, "TFLOPs": 2.0 * M * V * d / t / 1e12, "frac": 2.0 * M * V * d / t / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        del y, out
+    r = rows["4096"]
+    roof = {"bound": "mfma", "achieved": r["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": r["frac"],
+            "traffic": None, "kernel": "vendor library GEMM (torch.matmul, bf16 in, bf16 out)", "kernel_ms": r["us"] * 1e-3,
+            "by_rows": rows}
+    return _line("vendor library bf16 GEMM on the LM head's contraction (context, not the path), TFLOP/s on 1 GPU",
+                 r["TFLOPs"], "TFLOP/s", args, r["us"] * 1e-6 * args.steps, "bf16",
+                 f"y[4096 x {d}] W_lm[{V} x {d}]^T, plain GEMM without logit state or reduction", roof, None)
 
 
 def bench_tbody(args, np, torch, mi, mrp) -> dict:
@@ -399,7 +424,7 @@ def chain_line(res: dict, args) -> dict:
 
 def main() -> int:
     ap = argparse.ArgumentParser()
-    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody", "lm_traffic"],
+    ap.add_argument("--workload", default="chain", choices=["chain", "kl_loss", "residual_rms", "tbody", "lm_traffic", "library_gemm"],
                     help="chain (default): the headline metric; the others time further entry points")
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
@@ -433,7 +458,7 @@ def main() -> int:
 
     if args.workload != "chain":
         fn = {"kl_loss": bench_kl_loss, "residual_rms": bench_residual_rms, "tbody": bench_tbody,
-              "lm_traffic": bench_lm_traffic}[args.workload]
+              "lm_traffic": bench_lm_traffic, "library_gemm": bench_library_gemm}[args.workload]
         print(json.dumps(fn(args, np, torch, mi, mrp)))
         return 0
 
