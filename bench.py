@@ -366,9 +366,11 @@ def run_chain_config(cfg, args, np, torch, mi, mrp) -> dict:
     roof["traffic_source"] = (f"profiles/lm_head_cfg{cfg.cid}_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an earlier "
                               "run of this command, scaled by what the counters read for a 1 GiB copy; not measured in this run"
                               if roof["traffic"] is not None else None)
-    roof["kernel"] = (("lm_persist_kernel_32rows" if M <= 32 else "lm_persist_kernel_64rows" if M <= 64 else "lm_persist_kernel")
-                      if M <= 128 and V % 4 == 0 else
-                      "tiled_gemm_kernel<EPI_LM>" if M > 256 and V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
+    roof["kernel"] = (("lm_persist_kernel_32rows" if M <= 32 else "lm_persist_kernel_64rows" if M <= 64 else
+                       "lm_persist_kernel" if M <= 128 else "lm_persist_kernel_256rows")
+                      if M <= 256 and V % 4 == 0 else
+                      "lm_persist_kernel_256rows (+ a second launch for the rows beyond 256)" if M <= 512 and V % 4 == 0 else
+                      "tiled_gemm_kernel<EPI_LM>" if V % 4 == 0 else "stream_gemm_kernel<EPI_LM>")
     roof["kernel_ms"] = lm_avg_ms
     roof["launches"] = len(lm_ms)
     roof["algorithmic_bytes_per_launch"] = lm_bytes

@@ -1,4 +1,4 @@
-// Persistent LM-head kernel for up to 128 activation rows (the HBM-bound case of
+// Persistent LM-head kernel for up to 256 activation rows (the HBM-bound case of
 // the MRP chain): z <- z + y W_lm^T fused with the split-vocabulary
 // (max, sum-exp, argmax) partials (paper Section 3.2: the head reuses the
 // backbone's LM head; Algorithm 2: l <- l + delta; Section 2: confidence is the
@@ -28,7 +28,6 @@ __device__ __forceinline__ bf16x8 as_frag(const u32x4 &u) { return __builtin_bit
 
 constexpr int LM_WAVES = 8;
 constexpr int LM_THREADS = 64 * LM_WAVES;
-constexpr int LM_IT_MAX = 4;                   // up to 4 x 32 activation rows
 #ifndef MRP_LM_RING
 #define MRP_LM_RING 3
 #endif
@@ -38,10 +37,12 @@ static_assert(LM_RING == 2 || LM_RING == 3, "ring depth");
 // LM_IT: 32-row blocks of activation rows that are computed (1, 2 or 4: a launch with at most 32 or 64 rows
 // skips the matrix-core and LDS work of the empty blocks, which the 128-row form only just hides behind its
 // memory time)
-template <int LM_IT>
+// KS: 16-wide k blocks per activation stage and weight ring slot (8; 4 in the 256-row form, whose 128
+// accumulators leave room for half the ring)
+template <int LM_IT, int KS>
 __device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
     constexpr int LM_ROWS = 32 * LM_IT;
-    constexpr int LM_STAGE = KSTEP * LM_IT * 64;   // u32x4 per activation stage (32 KiB at 4 blocks)
+    constexpr int LM_STAGE = KS * LM_IT * 64;      // u32x4 per activation stage (32 KiB)
     constexpr int LM_NLD = LM_STAGE / LM_THREADS;  // u32x4 per thread per stage
     extern __shared__ u32x4 smem[];
     // reduction scratch, one copy per pass parity (a pass may end one iteration after the last)
@@ -68,7 +69,7 @@ __device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
         active = (p < P) && (wave < n);
         return rb_begin + o + wave;
     };
-    const int nkr = a.KB / KSTEP;
+    const int nkr = a.KB / KS;
     const int T = P * nkr;
     const int T3 = (T + LM_RING - 1) / LM_RING * LM_RING;  // padded: the tail iterations only re-load
     const u32x4 *Wp = reinterpret_cast<const u32x4 *>(a.Wp);
@@ -97,11 +98,11 @@ __device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
         wsrc = Wp + (act ? (size_t)rb * a.KB * 64 : (size_t)0) + lane;
         wmul = act ? 1 : 0;
     };
-    u32x4 wreg[LM_RING][KSTEP];
+    u32x4 wreg[LM_RING][KS];
 #define LM_WLOAD(slot)                                                                   \
     {                                                                                    \
-        _Pragma("unroll") for (int j = 0; j < KSTEP; ++j)                                \
-            wreg[slot][j] = wsrc[(size_t)((gw * KSTEP + j) * wmul) * 64];                 \
+        _Pragma("unroll") for (int j = 0; j < KS; ++j)                                \
+            wreg[slot][j] = wsrc[(size_t)((gw * KS + j) * wmul) * 64];                 \
         if (++gw == nkr) { gw = 0; ++pw; wcursor_set(); }                                \
     }
     // activation stage g (the same in every pass)
@@ -110,7 +111,7 @@ __device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
     _Pragma("unroll") for (int n = 0; n < LM_NLD; ++n) {                                 \
         const int c = tid + LM_THREADS * n;                                              \
         const int j = c / (LM_IT * 64), rem = c % (LM_IT * 64);                          \
-        st[n] = Yp[((size_t)((g) * KSTEP + j) * a.nIb) * 64 + rem];                      \
+        st[n] = Yp[((size_t)((g) * KS + j) * a.nIb) * 64 + rem];                      \
     }
 
     f32x16 acc[LM_IT];
@@ -211,7 +212,7 @@ __device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
         const u32x4 *cur = smem + buf * LM_STAGE;
         if (act_cur) {
 #pragma unroll
-            for (int j = 0; j < KSTEP; ++j) {
+            for (int j = 0; j < KS; ++j) {
                 bf16x8 bfr[LM_IT];
 #pragma unroll
                 for (int it = 0; it < LM_IT; ++it) bfr[it] = as_frag(cur[(j * LM_IT + it) * 64 + lane]);
@@ -264,28 +265,32 @@ __device__ __forceinline__ void lm_persist_body(const LmPersistArgs &a) {
 
 __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel(
     const LmPersistArgs a) {
-    lm_persist_body<4>(a);
+    lm_persist_body<4, 8>(a);
+}
+__global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel_256rows(
+    const LmPersistArgs a) {
+    lm_persist_body<8, 4>(a);
 }
 __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel_64rows(
     const LmPersistArgs a) {
-    lm_persist_body<2>(a);
+    lm_persist_body<2, 8>(a);
 }
 __global__ __launch_bounds__(LM_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void lm_persist_kernel_32rows(
     const LmPersistArgs a) {
-    lm_persist_body<1>(a);
+    lm_persist_body<1, 8>(a);
 }
 
 }  // namespace
 
-// (sized for the 128-row form; the smaller forms use less)
-size_t lm_persist_lds_bytes() {
-    return (size_t)2 * KSTEP * LM_IT_MAX * 64 * 16 + (size_t)2 * LM_WAVES * 32 * LM_IT_MAX * 12;
-}
+// two 32 KiB activation stages + two copies of the reduction scratch (sized for the 256-row form; the
+// smaller forms use less)
+size_t lm_persist_lds_bytes() { return (size_t)2 * 32768 + (size_t)2 * LM_WAVES * 256 * 12; }
 
 // Once per device (mrp_create): the kernels need more than the default 64 KiB of dynamic LDS.
 hipError_t lm_persist_configure() {
     hipError_t e = hipSuccess;
     for (const void *k : {reinterpret_cast<const void *>(lm_persist_kernel),
+                          reinterpret_cast<const void *>(lm_persist_kernel_256rows),
                           reinterpret_cast<const void *>(lm_persist_kernel_64rows),
                           reinterpret_cast<const void *>(lm_persist_kernel_32rows)})
         if (e == hipSuccess)
@@ -294,7 +299,9 @@ hipError_t lm_persist_configure() {
 }
 
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st) {
-    auto k = a.M <= 32 ? lm_persist_kernel_32rows : (a.M <= 64 ? lm_persist_kernel_64rows : lm_persist_kernel);
+    if (a.M > 256) return hipErrorInvalidValue;
+    auto k = a.M <= 32 ? lm_persist_kernel_32rows
+                       : (a.M <= 64 ? lm_persist_kernel_64rows : (a.M <= 128 ? lm_persist_kernel : lm_persist_kernel_256rows));
     hipLaunchKernelGGL(k, dim3(a.nWG), dim3(LM_THREADS), lm_persist_lds_bytes(), st, a);
     return hipGetLastError();
 }

@@ -21,7 +21,7 @@ struct mrp_ctx {
     size_t part_rows;   // capacity of the k-split partial buffer, in rows of d floats
     int maxB;
     bool use_tiled;     // 256 x 256 tiled GEMMs for M >= 768
-    bool lm_persist;    // the persistent LM-head kernel for M <= 128
+    bool lm_persist;    // the persistent LM-head kernel for M <= 512 (launches of at most 256 rows)
     int nCU;            // compute units of the device (workgroups of the persistent LM-head kernel)
     char *ws;
     size_t ws_bytes;
@@ -465,12 +465,12 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         const mrp_head &hd = heads[k - 1];
         StreamGemmArgs g;
         // 256 x 256 tiles pay off once there are enough of them to fill the chip more than once: from 768
-        // rows for the head body's GEMMs.  The LM head has V / 256 tiles per 256 rows; the streaming kernel
-        // takes the rows in groups of 256 and its time doubles with a second group, so the tile kernel is
-        // ahead from 257 rows on (measured at d = 4096, V = 151936: 930 / 952 / 1031 us at 256 / 512 / 752
-        // rows against 590 us at 256 and 1050 us at 384 rows)
+        // rows for the head body's GEMMs.  The LM head has V / 256 tiles per 256 rows and takes the tile kernel
+        // beyond 512 rows (measured at d = 4096, V = 151936: 931 / 955 / 1031 / 1074 us at 272 / 512 / 752 /
+        // 768 rows); below, the persistent kernel in launches of at most 256 rows is ahead (see there).  The
+        // streaming kernel is left with vocabularies that are not a multiple of 4.
         const bool tiled = c->use_tiled && M >= 768;
-        const bool tiled_lm = c->use_tiled && M > 256;
+        const bool tiled_lm = c->use_tiled && M > 512;
         int nks1 = 1, nks2 = 1;
         const float *resid = nullptr;   // transformer body: residual stream added to the last projection
         if (fused) {
@@ -585,20 +585,28 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         if (prof) HIP_TRY(c, hipEventRecord(c->ev[2 * c->ev_used], st));
         int nT_lm = 0;
         bool lm_rowmajor = false;  // partial layout [M][nT] (persistent kernel) or [nT][M]
-        if (c->lm_persist && M <= 128 && V % 4 == 0) {
-            LmPersistArgs la;
-            memset(&la, 0, sizeof(la));
-            la.Wp = static_cast<const uint4 *>(W_lm_packed);
-            la.Y = c->Y;
-            la.KB = d / 16; la.n_rb = (V + 31) / 32; la.nIb = c->nIb;
-            la.M = M; la.V = V;
-            la.nWG = c->nCU;
-            // consecutive heads walk the vocabulary in opposite directions: what the previous head
-            // touched last (W_lm is shared by all heads) is still in the L2s when this one starts
-            la.reverse = (off + k) & 1;
-            la.z = z; la.pm = c->pm; la.ps = c->ps; la.pi = c->pi;
-            HIP_TRY(c, launch_lm_persist(la, st));
-            nT_lm = la.nWG;
+        if (c->lm_persist && M <= 512 && V % 4 == 0) {
+            // up to 256 rows per launch; a second launch for the rows beyond streams W_lm again, which up to
+            // 512 rows is still cheaper than the tile kernel (measured at d = 4096: 392 us for 256 rows,
+            // 281 us for 128, against 931-955 us for the tile kernel at 272-512 rows)
+            int chunk = 0;
+            for (int row0 = 0; row0 < M; row0 += 256, ++chunk) {
+                LmPersistArgs la;
+                memset(&la, 0, sizeof(la));
+                la.Wp = static_cast<const uint4 *>(W_lm_packed);
+                la.Y = c->Y + (size_t)(row0 / 32) * 64;      // (planes are [k block][row block][lane])
+                la.KB = d / 16; la.n_rb = (V + 31) / 32; la.nIb = c->nIb;
+                la.M = M - row0 < 256 ? M - row0 : 256; la.V = V;
+                la.nWG = c->nCU;
+                // consecutive launches walk the vocabulary in opposite directions: what the previous one
+                // touched last (W_lm is shared by all heads) is still in the L2s when this one starts
+                la.reverse = (off + k + chunk) & 1;
+                la.z = z + (size_t)row0 * V;
+                la.pm = c->pm + (size_t)row0 * la.nWG; la.ps = c->ps + (size_t)row0 * la.nWG;
+                la.pi = c->pi + (size_t)row0 * la.nWG;
+                HIP_TRY(c, launch_lm_persist(la, st));
+            }
+            nT_lm = c->nCU;
             lm_rowmajor = true;
         } else if (tiled_lm && V % 4 == 0) {
             TiledGemmArgs tg;
