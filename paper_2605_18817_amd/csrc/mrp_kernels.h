@@ -106,7 +106,8 @@ struct HeadFusedArgs {
     float *U;                  // [M][d] fp32 u = W2 s
     int nIb, M, d;
     int *err_flag;
-    int nct, nrt;              // feature tiles d / 32, row tiles ceil(M / 32)
+    int nf;                    // weight row blocks per tile (1 or 2)
+    int nct, nrt;              // feature tiles d / (32 nf), row tiles ceil(M / 32)
 };
 
 // row-reduction partial: running max, sum of exp(x - max), index of the max
@@ -323,7 +324,8 @@ struct SmallGemmArgs {
     int nplanes;               // 1 or 2
     float *out;                // [M][R]
     int nIb, M, R, Kc;
-    int nct, nrt;              // feature tiles R / 32, row tiles ceil(M / 32)
+    int nf;                    // weight row blocks per tile (1 or 2; R % (32 nf) == 0)
+    int nct, nrt;              // feature tiles R / (32 nf), row tiles ceil(M / 32)
 };
 hipError_t launch_small_gemm(const SmallGemmArgs &a, hipStream_t st);
 hipError_t launch_head_fused(const HeadFusedArgs &a, hipStream_t st);   // both GEMMs: S and U written
