@@ -82,7 +82,8 @@ Layout make_layout(const mrp_dims *dm, int nCU) {
     l.nT_max = nT_lm > nT_0 ? nT_lm : nT_0;
     const int nT_p = nCU;  // persistent LM-head kernel: one slot per workgroup
     if (nT_p > l.nT_max) l.nT_max = nT_p;
-    l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 16 : (dm->max_rows < 2048 ? 2048 : dm->max_rows);
+    // (k-split partial sums: 16 parts at up to 128 rows; beyond, 4096 rows hold 4 parts of 1024 rows or 2 of 2048)
+    l.part_rows = dm->max_rows <= 128 ? (size_t)dm->max_rows * 16 : (dm->max_rows < 4096 ? 4096 : dm->max_rows);
     l.maxB = dm->max_rows / dm->block_len;
     size_t o = 0;
     auto take = [&](size_t bytes) { size_t r = o; o = align_up(o + bytes, 256); return r; };
@@ -162,9 +163,10 @@ int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, cons
         tg.seg[0] = TiledSeg{act, plane_stride, Kc / 64, nplanes};
         tg.nseg = 1;
         tg.nMt = (M + 255) / 256; tg.nVt = R / 256;
+        tg.nKs = tiled_ksplit(tg.nMt * tg.nVt, (Kc / 64) * nplanes, c->nCU, out_floats / (size_t)R, M);
         tg.out = out;
         *err = launch_tiled_gemm(tg, EPI_PARTIAL, st);
-        return *err == hipSuccess ? 1 : -1;
+        return *err == hipSuccess ? tg.nKs : -1;
     }
     if (small_rows_kernel(M, Kc) && R % 32 == 0 && Kc % 128 == 0 && nplanes <= 2) {
         SmallGemmArgs sg;
@@ -508,6 +510,8 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             tg.seg[1] = TiledSeg{c->XE, 0, d / 64, 1};
             tg.nseg = 2;
             tg.nMt = (M + 255) / 256; tg.nVt = (d + 255) / 256;
+            tg.nKs = tiled_ksplit(tg.nMt * tg.nVt, (d / 64) * (np_h + 1), c->nCU, c->part_rows, M);
+            nks1 = tg.nKs;
             tg.out = c->PART;
             HIP_TRY(c, launch_tiled_gemm(tg, EPI_PARTIAL, st));
         } else {
@@ -571,6 +575,8 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             tg.seg[0] = TiledSeg{c->S, c->plane, d / 64, NSPLIT};
             tg.nseg = 1;
             tg.nMt = (M + 255) / 256; tg.nVt = (d + 255) / 256;
+            tg.nKs = tiled_ksplit(tg.nMt * tg.nVt, (d / 64) * NSPLIT, c->nCU, c->part_rows, M);
+            nks2 = tg.nKs;
             tg.out = c->PART;
             HIP_TRY(c, launch_tiled_gemm(tg, EPI_PARTIAL, st));
         } else {
@@ -627,6 +633,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             tg.seg[0] = TiledSeg{c->Y, 0, d / 64, 1};
             tg.nseg = 1;
             tg.nMt = (M + 255) / 256; tg.nVt = (V + 255) / 256;
+            tg.nKs = 1;
             tg.z = z; tg.pm = c->pm; tg.ps = c->ps; tg.pi = c->pi;
             HIP_TRY(c, launch_tiled_gemm(tg, EPI_LM, st));
             nT_lm = tg.nVt;

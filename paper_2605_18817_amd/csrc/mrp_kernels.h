@@ -82,6 +82,7 @@ struct TiledGemmArgs {
     TiledSeg seg[2];
     int nseg;
     int nMt, nVt;        // tiles along activation rows / weight rows
+    int nKs;             // k parts (EPI_PARTIAL only: part ks writes out[ks][M][R]; 1 for EPI_LM)
     float *out;          // EPI_PARTIAL: [M][R]
     float *z;            // EPI_LM: [M][R] in/out, partials [nVt][M]
     float *pm, *ps;
@@ -238,6 +239,8 @@ hipError_t stream_gemm_configure();   // once per device
 int stream_gemm_it(int M);   // activation row blocks per workgroup for M rows
 
 hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st);
+// k parts for a partial-sum tile GEMM with `tiles` output tiles and `nsteps` k steps, writing at most `cap_rows` rows
+int tiled_ksplit(int tiles, int nsteps, int nCU, size_t cap_rows, int M);
 hipError_t launch_lm_persist(const LmPersistArgs &a, hipStream_t st);
 size_t lm_persist_lds_bytes();
 hipError_t lm_persist_configure();    // once per device

@@ -70,9 +70,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     const int ln = lane & 31, lh = lane >> 5;
 
     // ---- workgroup -> tile (XCD-aware) ----
+    // (with a k split every (tile block, k part) pair is a block of its own, so that few tiles still spread
+    //  over all XCDs)
     const int x = blockIdx.x & 7, s = blockIdx.x >> 3;
-    const int sb = (s >> 5) * 8 + x, t = s & 31;
+    const int sbk = (s >> 5) * 8 + x, t = s & 31;
     const int nMgrp = (a.nMt + 3) >> 2;
+    const int nsb = nMgrp * ((a.nVt + 7) >> 3);
+    const int sb = sbk % nsb, ks = sbk / nsb;
+    if (ks >= a.nKs) return;
     const int mgrp = sb % nMgrp, vchunk = sb / nMgrp;
     const int mt = mgrp * 4 + (t & 3), vt = vchunk * 8 + (t >> 2);
     if (mt >= a.nMt || vt >= a.nVt) return;
@@ -91,7 +96,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 
     // k-step sequence: segments x (k quads) x planes
     const int seg0_steps = a.seg[0].nkq * a.seg[0].nplanes;
-    const int nsteps = seg0_steps + (a.nseg > 1 ? a.seg[1].nkq * a.seg[1].nplanes : 0);
+    const int nsteps_all = seg0_steps + (a.nseg > 1 ? a.seg[1].nkq * a.seg[1].nplanes : 0);
+    const int nsteps = nsteps_all / a.nKs;          // this k part's steps (the host makes the split even)
+    const int st_begin = ks * nsteps, st_end = st_begin + nsteps;
     // Cursor over the k steps (segment, k quad, plane), advanced one step at a time without
     // divisions; it stops on the last step, which the padded tail re-fetches.  The segment
     // descriptions are copied out of the kernel arguments once (and made opaque, so that they
@@ -103,7 +110,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
     asm volatile("" : "+s"(seg_base0), "+s"(seg_base1), "+s"(seg_ps0), "+s"(seg_ps1), "+s"(seg_np0), "+s"(seg_np1),
                  "+s"(seg_nkq0));
     const long kq_stride = (long)TG_KB * a.nIb * 64;   // u32x4 per k quad of a plane
-    int cu_st = 0, cu_seg = 0, cu_kq = 0, cu_p = 0;
+    int cu_st = st_begin, cu_seg = 0, cu_kq = 0, cu_p = 0;
+    if (st_begin > 0) {      // where this k part starts: steps run over (segment, k quad, plane)
+        cu_seg = st_begin >= seg0_steps ? 1 : 0;
+        const int sl = cu_seg ? st_begin - seg0_steps : st_begin, np = cu_seg ? seg_np1 : seg_np0;
+        cu_kq = sl / np;
+        cu_p = sl % np;
+    }
     auto cursor_get = [&](int &kbw, const u32x4 *&bptr) __attribute__((always_inline)) {
         kbw = ((cu_seg ? seg_nkq0 : 0) + cu_kq) * TG_KB;
         const long base = cu_seg ? seg_base1 : seg_base0;
@@ -111,7 +124,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
         bptr = reinterpret_cast<const u32x4 *>(base) + (cu_p * ps + cu_kq * kq_stride + (long)ib0 * 64);
     };
     auto cursor_next = [&]() __attribute__((always_inline)) {
-        if (cu_st + 1 < nsteps) {
+        if (cu_st + 1 < st_end) {
             ++cu_st;
             if (++cu_p == (cu_seg ? seg_np1 : seg_np0)) {
                 cu_p = 0;
@@ -287,7 +300,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                 for (int q = 0; q < 4; ++q) {
                     const int r = (rb0 + wave * 2 + v2) * 32 + 8 * q + 4 * lh;
                     if (i < a.M && r < a.R)
-                        *reinterpret_cast<float4 *>(a.out + (size_t)i * a.R + r) = make_float4(
+                        *reinterpret_cast<float4 *>(a.out + ((size_t)ks * a.M + i) * a.R + r) = make_float4(
                             acc[v2][ib][4 * q], acc[v2][ib][4 * q + 1], acc[v2][ib][4 * q + 2], acc[v2][ib][4 * q + 3]);
                 }
             }
@@ -370,7 +383,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
 template <int EPI, int REM>
 hipError_t launch_inst(const TiledGemmArgs &a, hipStream_t st) {
     const int nMgrp = (a.nMt + 3) / 4, nVch = (a.nVt + 7) / 8;
-    const int nsb = nMgrp * nVch;
+    const int nsb = nMgrp * nVch * a.nKs;
     const int per_xcd = (nsb + 7) / 8;          // super-blocks per XCD
     const int grid = per_xcd * 32 * 8;
     hipLaunchKernelGGL((tiled_gemm_kernel<EPI, REM>), dim3(grid), dim3(256), 0, st, a);
@@ -381,13 +394,26 @@ template <int EPI>
 hipError_t launch_epi(const TiledGemmArgs &a, hipStream_t st) {
     int nsteps = 0;
     for (int sg = 0; sg < a.nseg; ++sg) nsteps += a.seg[sg].nkq * a.seg[sg].nplanes;
-    const int rem = 2 + (nsteps - 2) % 3;       // (at least two k steps: d >= 128)
+    if (a.nKs < 1 || nsteps % a.nKs != 0 || nsteps / a.nKs < 2 || (EPI == EPI_LM && a.nKs != 1)) return hipErrorInvalidValue;
+    nsteps /= a.nKs;
+    const int rem = 2 + (nsteps - 2) % 3;       // (at least two k steps per part)
     if (rem == 2) return launch_inst<EPI, 2>(a, st);
     if (rem == 3) return launch_inst<EPI, 3>(a, st);
     return launch_inst<EPI, 4>(a, st);
 }
 
 }  // namespace
+
+// Few output tiles (the head body's GEMMs at 1024 or 2048 rows have 64 or 128) leave most CUs idle: split k
+// into 2 or 4 parts so that tiles x parts comes near the CU count; every part must have an equal number of at
+// least 8 k steps and its partial sums must fit the buffer.
+int tiled_ksplit(int tiles, int nsteps, int nCU, size_t cap_rows, int M) {
+    int ks = 1;
+    while (ks < 4 && tiles * ks * 2 <= nCU && nsteps % (ks * 2) == 0 && nsteps / (ks * 2) >= 8 &&
+           (size_t)(ks * 2) * M <= cap_rows)
+        ks *= 2;
+    return ks;
+}
 
 hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st) {
     return epi == EPI_LM ? launch_epi<EPI_LM>(a, st) : launch_epi<EPI_PARTIAL>(a, st);
