@@ -134,15 +134,16 @@ int pick_ksplit(int nVt, int nMg, int G, size_t part_rows, int M) {
     return want < 1 ? 1 : want;
 }
 
-// Below the 256 x 256 tile kernel's range: the GEMM kernels that reduce their k split inside the workgroup
-// (no partial sums in memory).  The streaming kernel with its partial sums stays ahead only for wide
-// operands whose row count fills its 256-row groups (measured on the MLP body at d = 4096: 150 / 205 us per
-// head at 256 / 512 rows against 154 / 251 us, but 271 / 385 us at 384 / 640 rows against 206 / 336 us; at
-// d = 2048 it is behind everywhere: 102 / 133 / 160 us at 256 / 512 / 640 rows against 76 / 105 / 128 us).
-bool small_rows_kernel(int M, int Kc) {
-    const int last_group_empty = (M + 255) / 256 * 256 - M;
-    return M < 768 && (M <= 128 || Kc <= 2048 || last_group_empty >= 64);
-}
+// Which GEMM kernel the head body (and the transformer body's projections) take for M rows and operands of
+// width Kc.  The 256 x 256 tile kernel (with its k split when the tiles are few) from 768 rows, for wide
+// operands from 513; below, the kernels that reduce their k split inside the workgroup (no partial sums in
+// memory).  Measured per head of the MLP body, small-row kernels against the tile kernel: d = 4096 153 / 156 /
+// 208 / 254 / 294 us at 192 / 256 / 384 / 512 / 640 rows against 248 / 272 / 240 / 258 / 226 us; d = 2048 63 /
+// 103 / 128 us at 256 / 512 / 640 rows against 119 / 120 / 145 us.  (The streaming kernel with its partial
+// sums is behind both: d = 2048 102 / 133 / 160 us at 256 / 512 / 640 rows, d = 4096 202 / 268 / 329 us at
+// 256 / 512 / 752 rows.)
+bool body_on_tiles(int M, int Kc) { return M >= 768 || (Kc > 2048 && M > 512); }
+bool small_rows_kernel(int M, int Kc) { return !body_on_tiles(M, Kc); }
 
 // Weight row blocks per tile of the small-row GEMM kernels: two (64 features), so that a workgroup's
 // activation fragments serve twice the weights, once there are more 32-feature tiles than CUs and at least
@@ -155,7 +156,7 @@ int small_tile_blocks(int R, int nrt, int nCU) { return (R % 64 == 0 && (R / 32)
 // of k splits written (1 for the tiled kernel) or -1 after a launch error (*err set).
 int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, const uint4 *act, long plane_stride,
                  int nplanes, int M, float *out, size_t out_floats, hipError_t *err) {
-    if (c->use_tiled && M >= 768 && R % 256 == 0) {
+    if (c->use_tiled && body_on_tiles(M, Kc) && R % 256 == 0) {
         TiledGemmArgs tg;
         memset(&tg, 0, sizeof(tg));
         tg.Wp = static_cast<const uint4 *>(Wp);
@@ -475,12 +476,11 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
     for (int k = 1; k <= K; ++k) {
         const mrp_head &hd = heads[k - 1];
         StreamGemmArgs g;
-        // 256 x 256 tiles pay off once there are enough of them to fill the chip more than once: from 768
-        // rows for the head body's GEMMs.  The LM head has V / 256 tiles per 256 rows and takes the tile kernel
-        // beyond 512 rows (measured at d = 4096, V = 151936: 931 / 955 / 1031 / 1074 us at 272 / 512 / 752 /
-        // 768 rows); below, the persistent kernel in launches of at most 256 rows is ahead (see there).  The
-        // streaming kernel is left with vocabularies that are not a multiple of 4.
-        const bool tiled = c->use_tiled && M >= 768;
+        // The LM head has V / 256 tiles per 256 rows and takes the tile kernel beyond 512 rows (measured at
+        // d = 4096, V = 151936: 931 / 955 / 1031 / 1074 us at 272 / 512 / 752 / 768 rows); below, the persistent
+        // kernel in launches of at most 256 rows is ahead (see there).  The streaming kernel is left with
+        // vocabularies that are not a multiple of 4.
+        const bool tiled = c->use_tiled && body_on_tiles(M, d);
         const bool tiled_lm = c->use_tiled && M > 512;
         int nks1 = 1, nks2 = 1;
         const float *resid = nullptr;   // transformer body: residual stream added to the last projection

@@ -405,11 +405,14 @@ hipError_t launch_epi(const TiledGemmArgs &a, hipStream_t st) {
 }  // namespace
 
 // Few output tiles (the head body's GEMMs at 1024 or 2048 rows have 64 or 128) leave most CUs idle: split k
-// into 2 or 4 parts so that tiles x parts comes near the CU count; every part must have an equal number of at
-// least 8 k steps and its partial sums must fit the buffer.
+// into up to 16 parts so that tiles x parts comes near the CU count; every part must have an equal number of at
+// least MRP_TILED_MIN_STEPS k steps and its partial sums must fit the buffer.
+#ifndef MRP_TILED_MIN_STEPS
+#define MRP_TILED_MIN_STEPS 4
+#endif
 int tiled_ksplit(int tiles, int nsteps, int nCU, size_t cap_rows, int M) {
     int ks = 1;
-    while (ks < 4 && tiles * ks * 2 <= nCU && nsteps % (ks * 2) == 0 && nsteps / (ks * 2) >= 8 &&
+    while (ks < 16 && tiles * ks * 2 <= nCU && nsteps % (ks * 2) == 0 && nsteps / (ks * 2) >= MRP_TILED_MIN_STEPS &&
            (size_t)(ks * 2) * M <= cap_rows)
         ks *= 2;
     return ks;

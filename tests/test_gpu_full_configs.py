@@ -176,11 +176,10 @@ def test_config2_full_batch():
 @pytest.mark.timeout(900)
 @pytest.mark.parametrize("B", [16, 24, 32])
 def test_config2_middle_row_range(B):
-    """Between the persistent LM-head kernel (at most 128 rows) and the all-tiled path (768 rows and
-    more), at config 2's width (d = 4096): at 256 rows (B = 16) the LM head and the head GEMMs run on the
-    streaming kernel with its 256-row workgroups; at 384 rows (B = 24) the LM head runs on the tile kernel
-    and the head body on the small-row GEMMs; at 512 rows (B = 32) the LM head on the tile kernel and the
-    head body on the streaming kernel.  One sequence from every 256-row group."""
+    """Between config 1's and config 2's row counts at config 2's width (d = 4096): the LM head runs on the
+    persistent kernel's 256-row form, in one launch at 256 rows (B = 16) and in two at 384 and 512 rows
+    (B = 24, 32); the head body on the small-row GEMMs with 64-feature tiles.  One sequence from every
+    256-row group."""
     cfg = mi.config(2, B=B)
     assert 128 < cfg.M < 768
     prob, io, g, stats = _run_full(cfg, mrp.RevealCfg(tau=cfg.tau), seqs=one_sequence_per_row_tile(cfg))
