@@ -245,3 +245,22 @@ def test_empty_batch_and_errors():
         torch.cuda.synchronize()
     finally:
         prob.close()
+
+
+@pytest.mark.parametrize("d,B,L,K", [
+    (256, 129, 1, 2),    # one row past the 128-row LM-head form: its 256-row form, small-row head GEMMs (5 row tiles)
+    (256, 16, 16, 2),    # 256 rows: the 256-row form filled exactly
+    (256, 257, 1, 1),    # two LM-head launches (256 + 1 rows), 9 row tiles: 64-feature tiles
+    (256, 32, 16, 1),    # 512 rows: two full LM-head launches
+    (256, 513, 1, 1),    # one row past: the tile kernel for the LM head, small-row kernels for the body
+    (256, 59, 13, 1),    # 767 rows, the last row count of the small-row head body at this width
+    (4096, 25, 8, 2),    # wide model, 200 rows: 64-feature tiles, 7 row tiles, the last ragged
+    (4096, 37, 16, 1),   # wide model, 592 rows: tile kernel with k split for the head body (48 tiles x 4 parts)
+])
+def test_row_counts_where_the_kernels_change(d, B, L, K):
+    """Row counts on both sides of every switch between kernel families (LM head: 128 / 256 / 512 rows;
+    head body: 768 rows, 512 for d > 2048; 32- against 64-feature tiles), each against the oracle."""
+    V = 1028 if d > 256 else 4096 + 36
+    cfg = mi.straddling(mi.config(0, d=d, V=V, B=B, L=L, K=K))
+    prob, g, o, stats = _free_run(cfg, mrp.RevealCfg(tau=0.9, tau_remask=0.5), seqs=list(range(0, B, max(1, B // 5))))
+    prob.close()
