@@ -40,7 +40,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        _lib = C.CDLL(build())
+        # (MRP_ORACLE_LIB: a library to load instead -- only the planted-mistake test sets it, to show that
+        #  the pins fail on a deliberately wrong oracle)
+        _lib = C.CDLL(os.environ.get("MRP_ORACLE_LIB") or build())
         _lib.orc_bf16_round.restype = C.c_double
         _lib.orc_bf16_round.argtypes = [C.c_double]
         _lib.orc_max_accept_cap.restype = C.c_int

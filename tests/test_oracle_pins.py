@@ -405,6 +405,11 @@ def test_remask_set_inclusions():
     # rows revealed by the current state are not eligible
     ra = np.full(M, 2, np.int8); m = np.zeros(M, np.uint8)
     assert orc.remask(B, L, 2, conf, 1.5, None, m, ra).sum() == 0
+    # the comparison is strict (Algorithm 4: confidence below the threshold): a row exactly at the
+    # threshold stays revealed, the next smaller double is remasked
+    c2 = np.array([0.5, np.nextafter(0.5, 0.0), np.nextafter(0.5, 1.0), 0.5])
+    rem = orc.remask(1, 4, 1, c2, 0.5, None, np.zeros(4, np.uint8), np.zeros(4, np.int8))
+    np.testing.assert_array_equal(rem, [0, 1, 0, 0])
 
 
 def test_chain_remask_and_reveal_control_flow():
