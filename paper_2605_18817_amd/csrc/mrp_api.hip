@@ -483,6 +483,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
         const bool tiled = c->use_tiled && body_on_tiles(M, d);
         const bool tiled_lm = c->use_tiled && M > 512;
         int nks1 = 1, nks2 = 1;
+        bool silu_done = false;   // the first GEMM's epilogue already wrote s = SiLU(a) as activation planes
         const float *resid = nullptr;   // transformer body: residual stream added to the last projection
         if (fused) {
             // s = SiLU(W1 [h ; e]) with e read from the embedding table, then u = W2 s
@@ -513,7 +514,10 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             tg.nKs = tiled_ksplit(tg.nMt * tg.nVt, (d / 64) * (np_h + 1), c->nCU, c->part_rows, M);
             nks1 = tg.nKs;
             tg.out = c->PART;
-            HIP_TRY(c, launch_tiled_gemm(tg, EPI_PARTIAL, st));
+            // a single k part of the MLP body: SiLU and the fp16 split sit in the tile epilogue
+            silu_done = !layers && tg.nKs == 1;
+            tg.planes = c->S; tg.plane_stride = c->plane;
+            HIP_TRY(c, launch_tiled_gemm(tg, silu_done ? EPI_SILU : EPI_PARTIAL, st));
         } else {
             memset(&g, 0, sizeof(g));
             g.Wp = static_cast<const uint4 *>(hd.W1_packed);
@@ -565,7 +569,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
             nks2 = nks;
             resid = c->tb_U;
         } else {
-        HIP_TRY(c, launch_silu_split(c->PART, nks1, c->S, c->plane, c->nIb, M, d, st));
+        if (!silu_done) HIP_TRY(c, launch_silu_split(c->PART, nks1, c->S, c->plane, c->nIb, M, d, st));
         // u = W2 s
         if (tiled) {
             TiledGemmArgs tg;

@@ -35,7 +35,7 @@ struct ActSeg {
     int nplanes;
 };
 
-enum { EPI_PARTIAL = 0, EPI_LM = 1 };
+enum { EPI_PARTIAL = 0, EPI_LM = 1, EPI_SILU = 2 };
 
 struct StreamGemmArgs {
     const uint4 *Wp;   // packed weights [n_rb][KBw][64] uint4
@@ -83,7 +83,9 @@ struct TiledGemmArgs {
     int nseg;
     int nMt, nVt;        // tiles along activation rows / weight rows
     int nKs;             // k parts (EPI_PARTIAL only: part ks writes out[ks][M][R]; 1 for EPI_LM)
-    float *out;          // EPI_PARTIAL: [M][R]
+    float *out;          // EPI_PARTIAL: [nKs][M][R]
+    uint4 *planes;       // EPI_SILU: the NSPLIT fp16 planes [R / 16][nIb][64] of SiLU(X W^T), plane_stride apart
+    long plane_stride;
     float *z;            // EPI_LM: [M][R] in/out, partials [nVt][M]
     float *pm, *ps;
     int *pi;

@@ -17,7 +17,8 @@
 // block of 4 (activation) x 8 (weight) tiles and share its operand slices in that
 // XCD's L2.
 //
-// Epilogues: EPI_PARTIAL (fp32 tile to out[i][r]) and EPI_LM (the tile is added to the
+// Epilogues: EPI_PARTIAL (fp32 tile to out[i][r]; part ks of a k split to out[ks][i][r]), EPI_SILU (SiLU of the
+// tile as the two fp16 activation planes of the next GEMM; no k split) and EPI_LM (the tile is added to the
 // logit state, which is stored back, and the per-row (max, sum-exp, argmax) partial of
 // the tile's 256 vocabulary entries is written; paper Section 3.2 / Algorithm 2
 // l <- l + delta).
@@ -36,7 +37,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));   // native vector: arr
 // head bf16 ones.
 template <int EPI>
 __device__ __forceinline__ f32x16 mma_frag(const u32x4 &w, const u32x4 &x, const f32x16 &c) {
-    if constexpr (EPI == EPI_PARTIAL)
+    if constexpr (EPI != EPI_LM)
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, w), __builtin_bit_cast(f16x8, x), c, 0, 0, 0);
     else
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, x), c, 0, 0, 0);
@@ -304,6 +305,32 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) voi
                             acc[v2][ib][4 * q], acc[v2][ib][4 * q + 1], acc[v2][ib][4 * q + 2], acc[v2][ib][4 * q + 3]);
                 }
             }
+    } else if constexpr (EPI == EPI_SILU) {
+        // s = SiLU(tile) written as the two fp16 planes of the next GEMM's activation: a lane holds 4 of the
+        // 8 features of a 16-byte chunk (the lane ^ 32 holds the other 4), so it stores 8 bytes per plane;
+        // the 64 lanes' pieces of one (v2, ib, q) are 512 contiguous bytes
+        uint2 *planes = reinterpret_cast<uint2 *>(a.planes);
+#pragma unroll
+        for (int v2 = 0; v2 < 2; ++v2)
+#pragma unroll
+            for (int ib = 0; ib < 8; ++ib) {
+                const int i = (ib0 + ib) * 32 + lne;
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int c8 = (rb0 + wave * 2 + v2) * 4 + q;
+                    if (i < a.M && c8 * 8 < a.R) {
+                        uint16_t h[4], l[4];
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float x = acc[v2][ib][4 * q + e];
+                            split2(x / (1.0f + expf(-x)), h[e], l[e]);
+                        }
+                        const size_t o = 2 * act_chunk_index(i, c8, a.nIb) + lh;
+                        planes[o] = make_uint2(pack2(h[0], h[1]), pack2(h[2], h[3]));
+                        planes[o + 2 * a.plane_stride] = make_uint2(pack2(l[0], l[1]), pack2(l[2], l[3]));
+                    }
+                }
+            }
     } else {
         // per wave: 256 activation rows x 64 vocabulary entries.  The logit tile is added here, one
         // 32-row slice (32 registers) at a time; the row reduction over v runs in registers.
@@ -394,7 +421,7 @@ template <int EPI>
 hipError_t launch_epi(const TiledGemmArgs &a, hipStream_t st) {
     int nsteps = 0;
     for (int sg = 0; sg < a.nseg; ++sg) nsteps += a.seg[sg].nkq * a.seg[sg].nplanes;
-    if (a.nKs < 1 || nsteps % a.nKs != 0 || nsteps / a.nKs < 2 || (EPI == EPI_LM && a.nKs != 1)) return hipErrorInvalidValue;
+    if (a.nKs < 1 || nsteps % a.nKs != 0 || nsteps / a.nKs < 2 || (EPI != EPI_PARTIAL && a.nKs != 1)) return hipErrorInvalidValue;
     nsteps /= a.nKs;
     const int rem = 2 + (nsteps - 2) % 3;       // (at least two k steps per part)
     if (rem == 2) return launch_inst<EPI, 2>(a, st);
@@ -419,6 +446,7 @@ int tiled_ksplit(int tiles, int nsteps, int nCU, size_t cap_rows, int M) {
 }
 
 hipError_t launch_tiled_gemm(const TiledGemmArgs &a, int epi, hipStream_t st) {
+    if (epi == EPI_SILU) return launch_epi<EPI_SILU>(a, st);
     return epi == EPI_LM ? launch_epi<EPI_LM>(a, st) : launch_epi<EPI_PARTIAL>(a, st);
 }
 
