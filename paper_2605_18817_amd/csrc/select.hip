@@ -102,7 +102,7 @@ __device__ __forceinline__ bool more_confident(const float *conf, int a, int b) 
 __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
     __shared__ float s_conf[MAX_L], s_lse[MAX_L];
     __shared__ int s_tok[MAX_L], s_xtok[MAX_L];
-    __shared__ uint8_t s_mk[MAX_L], s_rem[MAX_L];
+    __shared__ uint8_t s_mk[MAX_L];
     __shared__ int8_t s_ra[MAX_L];
     __shared__ int s_gather;
     const int b = blockIdx.x, L = a.L;
@@ -196,21 +196,29 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
     }
     __syncthreads();
 
-    if (threadIdx.x == 0) {
-        int cand[MAX_L];
+    // The decision of the state, one lane per position (L <= 64: the first wavefront).  A still-masked
+    // position's rank is the number of still-masked positions that are more confident (ties: lower
+    // position first), so "the ns most confident" are the positions of rank < ns; the number above the
+    // threshold, the cap and the forced minimum are counted with ballots.  Same outcome as sorting the
+    // candidates and walking the sorted list, without a serial part.
+    if (wave == 0) {
+        const int p = lane;
+        const bool in = p < L;
+        bool mk = in && s_mk[in ? p : 0] != 0;
+        const float cf = in ? s_conf[p] : 0.f;
+        int ra = in ? (int)s_ra[p] : -1;
+        int xt = in ? s_xtok[p] : -1;
+        in_cond = __shfl(in_cond, 0);
+        in_prot = __shfl(in_prot, 0);
         int dpos = -1, dtok = -1, cond = in_cond, prot = in_prot;
         if (a.do_reveal) {
-            int nc = 0;
-            for (int p = 0; p < L; ++p)
-                if (s_mk[p]) cand[nc++] = p;
-            for (int x = 1; x < nc; ++x) {  // most confident first
-                const int p = cand[x];
-                int q = x - 1;
-                while (q >= 0 && more_confident(s_conf, p, cand[q])) { cand[q + 1] = cand[q]; --q; }
-                cand[q + 1] = p;
+            int rank = 0;
+            for (int q = 0; q < L; ++q) {
+                const float cq = s_conf[q];
+                if (s_mk[q] && (cq > cf || (cq == cf && q < p))) ++rank;
             }
-            int ns = 0;
-            while (ns < nc && s_conf[cand[ns]] > a.tau) ++ns;
+            const int nc = __popcll(__ballot(mk));
+            int ns = __popcll(__ballot(mk && cf > a.tau));
             if (a.max_accept) {
                 int m = (7 * nc) / 10;
                 if (m < 5) m = 5;
@@ -218,47 +226,47 @@ __global__ __launch_bounds__(256) void merge_select_kernel(const SelectArgs a) {
                 if (ns > m) ns = m;
             }
             if (ns < a.r_min) ns = a.r_min < nc ? a.r_min : nc;
-            for (int x = 0; x < ns; ++x) {
-                s_mk[cand[x]] = 0; s_ra[cand[x]] = (int8_t)a.state; s_xtok[cand[x]] = s_tok[cand[x]];
-            }
+            const unsigned long long top = __ballot(mk && rank == 0);
             if (ns > 0) {
-                dpos = cand[0];
-                dtok = s_tok[cand[0]];
+                dpos = __ffsll((long long)top) - 1;
+                dtok = s_tok[dpos];
                 cond = dtok;
-                a.cond_tok[b] = dtok;
+                if (lane == 0) a.cond_tok[b] = dtok;
             }
-            if (a.write_protect) { prot = dpos; a.protect_pos[b] = dpos; }
-        }
-        a.draft_pos[(size_t)b * a.draft_stride] = dpos;
-        a.draft_tok[(size_t)b * a.draft_stride] = dtok;
-        for (int p = 0; p < L; ++p) {
-            uint8_t rem = 0;
-            if (a.tau_remask >= 0.f) {
-                const int r = s_ra[p];
-                float cr = s_conf[p];
-                if (a.remask_mode == 1 && r >= 0 && r <= a.state - 1) {
-                    // probability of the token that was revealed here under the updated logits
-                    int t = s_xtok[p];
-                    if (t >= a.V && a.err_flag) atomicOr(a.err_flag, ERR_X_TOK);
-                    t = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
-                    cr = (s_xtok[p] >= 0) ? expf(a.z[(size_t)(b * L + p) * a.V + t] - s_lse[p]) : 0.f;
-                }
-                if (r >= 0 && r <= a.state - 1 && p != prot && cr < a.tau_remask) {
-                    s_mk[p] = 1; s_ra[p] = -1; rem = 1;
-                }
+            if (mk && rank < ns) { mk = false; ra = a.state; xt = s_tok[p]; }
+            if (a.write_protect) {
+                prot = dpos;
+                if (lane == 0) a.protect_pos[b] = dpos;
             }
-            s_rem[p] = rem;
         }
-        s_gather = cond;
+        if (lane == 0) {
+            a.draft_pos[(size_t)b * a.draft_stride] = dpos;
+            a.draft_tok[(size_t)b * a.draft_stride] = dtok;
+            s_gather = cond;
+        }
+        uint8_t rem = 0;
+        if (in && a.tau_remask >= 0.f) {
+            float cr = cf;
+            if (a.remask_mode == 1 && ra >= 0 && ra <= a.state - 1) {
+                // probability of the token that was revealed here under the updated logits
+                int t = xt;
+                if (t >= a.V && a.err_flag) atomicOr(a.err_flag, ERR_X_TOK);
+                t = t < 0 ? 0 : (t >= a.V ? a.V - 1 : t);
+                cr = (xt >= 0) ? expf(a.z[(size_t)(b * L + p) * a.V + t] - s_lse[p]) : 0.f;
+            }
+            if (ra >= 0 && ra <= a.state - 1 && p != prot && cr < a.tau_remask) {
+                mk = true; ra = -1; rem = 1;
+            }
+        }
+        if (in) {
+            a.masked[b * L + p] = mk ? 1 : 0;
+            a.revealed_at[b * L + p] = (int8_t)ra;
+            if (a.remasked) a.remasked[b * L + p] = rem;
+            if (a.x_tok) a.x_tok[b * L + p] = xt;
+        }
     }
     __syncthreads();
 
-    if (threadIdx.x < L) {
-        a.masked[b * L + threadIdx.x] = s_mk[threadIdx.x];
-        a.revealed_at[b * L + threadIdx.x] = s_ra[threadIdx.x];
-        if (a.remasked) a.remasked[b * L + threadIdx.x] = s_rem[threadIdx.x];
-        if (a.x_tok) a.x_tok[b * L + threadIdx.x] = s_xtok[threadIdx.x];
-    }
     if (a.E != nullptr) {  // embedding row that conditions the next head
         const int C8 = a.d >> 3;
         int tokc = s_gather;  // caller contract: 0 <= cond_tok < V; a bad value is clamped and reported
