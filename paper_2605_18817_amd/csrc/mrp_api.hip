@@ -44,6 +44,7 @@ struct mrp_ctx {
     float *tb_part;            // partial sums, tb_part_floats floats
     size_t tb_part_floats;
     float2 *tb_rope;           // [max_rows][64]
+    float *tb_attn;            // attention partials, attention_scratch_floats() floats
     char err[512];
     bool prof_on;
     std::vector<hipEvent_t> ev;  // pairs
@@ -347,6 +348,7 @@ int mrp_tbody_create(mrp_ctx *c, const mrp_tbody_dims *t) {
     const size_t off_P = take((size_t)NSPLIT * c->tb_plane * 16);
     const size_t off_part = take(c->tb_part_floats * sizeof(float));
     const size_t off_rope = take((size_t)c->dims.max_rows * 64 * sizeof(float2));
+    const size_t off_attn = take(attention_scratch_floats() * sizeof(float));
     if (hipMalloc(reinterpret_cast<void **>(&c->tb_ws), o) != hipSuccess || hipMemset(c->tb_ws, 0, o) != hipSuccess ||
         hipDeviceSynchronize() != hipSuccess) {
         if (c->tb_ws) (void)hipFree(c->tb_ws);
@@ -357,6 +359,7 @@ int mrp_tbody_create(mrp_ctx *c, const mrp_tbody_dims *t) {
     c->tb_P = reinterpret_cast<uint4 *>(c->tb_ws + off_P);
     c->tb_part = reinterpret_cast<float *>(c->tb_ws + off_part);
     c->tb_rope = reinterpret_cast<float2 *>(c->tb_ws + off_rope);
+    c->tb_attn = reinterpret_cast<float *>(c->tb_ws + off_attn);
     c->tb = *t;
     c->tb_on = true;
     return MRP_OK;
@@ -552,7 +555,7 @@ static int chain_impl(mrp_ctx *c, void *stream, int B, int K, const void *h, flo
                 HIP_TRY(c, launch_attention(c->tb_part, nks, M, B, L, tb.n_heads, tb.n_kv_heads, c->tb_rope,
                                             static_cast<const uint16_t *>(ly.k_cache),
                                             static_cast<const uint16_t *>(ly.v_cache), prefix_len, tb.max_prefix,
-                                            c->tb_P, c->tb_plane, c->nIb, st));
+                                            c->tb_P, c->tb_plane, c->nIb, c->tb_attn, st));
                 nks = gemm_partial(c, st, ly.Wo_packed, d, qd, c->tb_P, c->tb_plane, NSPLIT, M, c->PART, part_d, &ge);
                 HIP_TRY(c, ge);
                 // a = u + Wo o; planes <- RMSNorm(a) g2

@@ -319,7 +319,8 @@ hipError_t launch_swiglu_split(const float *part, int nKs, uint4 *planes, long p
                                hipStream_t st);
 hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int nh, int nkv, const float2 *rope,
                             const uint16_t *kc, const uint16_t *vc, const int32_t *prefix_len, int P_max,
-                            uint4 *o_planes, long plane_stride, int nIb, hipStream_t st);
+                            uint4 *o_planes, long plane_stride, int nIb, float *scratch, hipStream_t st);
+size_t attention_scratch_floats();   // floats of `scratch` (partials of workgroups that share a prefix)
 
 // out [M][R] fp32 = X W^T, k split reduced inside the workgroup (R % 32 == 0, Kc % 128 == 0)
 struct SmallGemmArgs {
