@@ -170,6 +170,18 @@ int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, cons
         *err = launch_tiled_gemm(tg, EPI_PARTIAL, st);
         return *err == hipSuccess ? tg.nKs : -1;
     }
+    if (small_rows_kernel(M, Kc) && M > 64 && R % 64 == 0 && nplanes <= 2) {
+        // 65 .. 512 rows: 64-feature x 128-row tiles with k split over workgroups
+        const int nft = R / 64, nrg = (M + 127) / 128;
+        const int ks = wide_gemm_ksplit(nft * nrg, Kc / 16, c->nCU, out_floats / (size_t)R, M);
+        if (ks > 0) {
+            WideGemmArgs wg;
+            wg.Wp = static_cast<const uint4 *>(Wp); wg.X = act; wg.plane = plane_stride; wg.nplanes = nplanes;
+            wg.out = out; wg.nIb = c->nIb; wg.M = M; wg.R = R; wg.Kc = Kc; wg.nKs = ks; wg.nft = nft; wg.nrg = nrg;
+            *err = launch_wide_gemm(wg, st);
+            return *err == hipSuccess ? ks : -1;
+        }
+    }
     if (small_rows_kernel(M, Kc) && R % 32 == 0 && Kc % 128 == 0 && nplanes <= 2) {
         SmallGemmArgs sg;
         sg.Wp = static_cast<const uint4 *>(Wp); sg.X = act; sg.plane = plane_stride; sg.nplanes = nplanes;

@@ -322,6 +322,20 @@ hipError_t launch_attention(const float *qkv, int nKs, int M, int B, int L, int 
                             uint4 *o_planes, long plane_stride, int nIb, float *scratch, hipStream_t st);
 size_t attention_scratch_floats();   // floats of `scratch` (partials of workgroups that share a prefix)
 
+// out [nKs][M][R] fp32 partial sums of X W^T on 64-feature x 128-row tiles (wide_gemm.hip)
+struct WideGemmArgs {
+    const uint4 *Wp;           // packed fp16 weights [R / 32][Kc / 16][64]
+    const uint4 *X;            // activation planes [Kc / 16][nIb][64]
+    long plane;                // plane stride (uint4 units)
+    int nplanes;               // 1 or 2
+    float *out;                // [nKs][M][R]
+    int nIb, M, R, Kc;
+    int nKs;                   // k parts (1, 2, 4 or 8)
+    int nft, nrg;              // R / 64 feature tiles, ceil(M / 128) row groups
+};
+int wide_gemm_ksplit(int tiles, int kbs, int nCU, size_t cap_rows, int M);   // 0: not applicable
+hipError_t launch_wide_gemm(const WideGemmArgs &a, hipStream_t st);
+
 // out [M][R] fp32 = X W^T, k split reduced inside the workgroup (R % 32 == 0, Kc % 128 == 0)
 struct SmallGemmArgs {
     const uint4 *Wp;           // packed fp16 weights [R / 32][Kc / 16][64]

@@ -126,6 +126,22 @@ def test_many_rows_tiled_gemm_path():
     _run(cfg, td, mrp.RevealCfg(tau=0.9), seqs=[0, 1, 17, 47])
 
 
+def test_160_rows_two_row_groups_of_the_wide_gemm():
+    """160 rows: the projections run on the 64-feature x 128-row tiles with a ragged second row group (32 of 128
+    rows) and k split over workgroups; 20 (kv head, sequence) pairs share their prefixes between two workgroups."""
+    cfg = mi.straddling(mi.config(0, d=512, B=10, L=16, K=2))
+    td = mi.TBodyDims(D=2, n_heads=4, n_kv_heads=2, head_dim=128, d_ff=512, P_max=300)
+    _run(cfg, td, mrp.RevealCfg(tau=0.9), seqs=[0, 4, 9])
+
+
+def test_long_prefix_shared_by_four_workgroups():
+    """Two (kv head, sequence) pairs with a 1024-position cache: four workgroups per pair; sequence 0 has no
+    prefix (its three extra workgroups write empty partials), sequence 1 a full one."""
+    cfg = mi.straddling(mi.config(0, d=256, B=2, L=8, K=1))
+    td = mi.TBodyDims(D=1, n_heads=2, n_kv_heads=1, head_dim=128, d_ff=256, P_max=1024)
+    _run(cfg, td, mrp.RevealCfg(tau=0.9))
+
+
 @pytest.mark.timeout(900)
 def test_config1_shape_three_layers():
     """Config 1's sizes with the backbone family's layer shape at that width (16 query / 8 kv heads
