@@ -58,8 +58,7 @@ __device__ __forceinline__ void spill_tile(float (*t)[LD], const f32x16 &acc, in
 // tile's first packed weight row block + lane, wstride: u32x4 between row blocks; x0: plane 0 + row block
 // offset + lane; k block kb of plane p is at x0 + p * pstride + kb * kstride.  The k blocks come in
 // chunks of HF_CH, one chunk fetched while the previous one is multiplied (weight fragments from HBM,
-// activation fragments from L2).  Deeper or wider prefetch does not pay: a CU's throughput here is set by
-// the misses its vector cache can track, not by this loop.
+// activation fragments from L2).
 template <int NF, int NP>
 __device__ __forceinline__ void wave_gemm_planes(f32x16 (&acc)[NF], const u32x4 *wrow, size_t wstride, int kb0,
                                                  const u32x4 *x0, long pstride, size_t kstride, int nj, int wave) {
@@ -85,11 +84,32 @@ __device__ __forceinline__ void wave_gemm_planes(f32x16 (&acc)[NF], const u32x4 
                     for (int f = 0; f < NF; ++f) acc[f] = mma16(w[buf][u][f], x[buf][u][p], acc[f]);
             }
     };
+    auto compute_whole = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < HF_CH; ++u)
+#pragma unroll
+            for (int p = 0; p < NP; ++p)
+#pragma unroll
+                for (int f = 0; f < NF; ++f) acc[f] = mma16(w[buf][u][f], x[buf][u][p], acc[f]);
+    };
+    // Whole pairs of chunks run without a condition on the fetches (past the end the last k block is fetched
+    // again and not used): a fetch under a condition makes the compiler wait for every load at the loop's end,
+    // and the scheduling barriers keep it from sinking the fetches below the MFMAs that hide them.
     fetch(0, 0);
-    for (int j0 = 0; j0 < nj; j0 += 2 * HF_CH) {
+    int j0 = 0;
+    for (; j0 + 2 * HF_CH <= nj; j0 += 2 * HF_CH) {
+        fetch(1, j0 + HF_CH);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_whole(0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(0, j0 + 2 * HF_CH);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_whole(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (j0 < nj) {     // fewer than two chunks left; set 0 holds the first of them
         if (j0 + HF_CH < nj) fetch(1, j0 + HF_CH);
         compute(0, j0);
-        if (j0 + 2 * HF_CH < nj) fetch(0, j0 + 2 * HF_CH);
         if (j0 + HF_CH < nj) compute(1, j0 + HF_CH);
     }
 }
@@ -120,11 +140,32 @@ __device__ __forceinline__ void wave_gemm_embed(f32x16 (&acc)[NF], const u32x4 *
                 for (int f = 0; f < NF; ++f) acc[f] = mma16(w[buf][u][f], __builtin_bit_cast(u32x4, fx), acc[f]);
             }
     };
+    auto compute_whole = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < HF_CH; ++u) {
+            const uint4 fx = bf16x8_to_f16x8(x[buf][u]);
+#pragma unroll
+            for (int f = 0; f < NF; ++f) acc[f] = mma16(w[buf][u][f], __builtin_bit_cast(u32x4, fx), acc[f]);
+        }
+    };
+    // Whole pairs of chunks run without a condition on the fetches (past the end the last k block is fetched
+    // again and not used): a fetch under a condition makes the compiler wait for every load at the loop's end,
+    // and the scheduling barriers keep it from sinking the fetches below the MFMAs that hide them.
     fetch(0, 0);
-    for (int j0 = 0; j0 < nj; j0 += 2 * HF_CH) {
+    int j0 = 0;
+    for (; j0 + 2 * HF_CH <= nj; j0 += 2 * HF_CH) {
+        fetch(1, j0 + HF_CH);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_whole(0);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(0, j0 + 2 * HF_CH);
+        __builtin_amdgcn_sched_barrier(0);
+        compute_whole(1);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (j0 < nj) {     // fewer than two chunks left; set 0 holds the first of them
         if (j0 + HF_CH < nj) fetch(1, j0 + HF_CH);
         compute(0, j0);
-        if (j0 + 2 * HF_CH < nj) fetch(0, j0 + 2 * HF_CH);
         if (j0 + HF_CH < nj) compute(1, j0 + HF_CH);
     }
 }
