@@ -8,7 +8,7 @@
 // The four projections run on the shared GEMM kernels (fp32 activations as two fp16 planes, fp32
 // partial sums); this file holds what sits between them: the residual-stream update with RMSNorm,
 // the gated activation, the rotary table and the attention kernel (fp32 on the vector ALU, and the
-// matrix cores with two-term fp16 operands for the two contractions over the prefix cache).
+// matrix cores with three-term bf16 operands for the two contractions over the prefix cache).
 #include "mrp_kernels.h"
 
 namespace mrp {
@@ -108,12 +108,13 @@ __global__ __launch_bounds__(256) void swiglu_split_kernel(const float *__restri
 }
 
 // ------------------------------------------------------------------------------------------------
-// Attention.  One workgroup (4 wavefronts) per (kv head g, sequence b): its Q = (nh / nkv) * L query
+// Attention.  One workgroup (NW = 8 or 4 wavefronts) per (kv head g, sequence b), or several that share
+// the pair's prefix: its Q = (nh / nkv) * L query
 // vectors (query qq = hrep * L + i: head g * rep + hrep, block row i) share the keys and values of
 // head g.
 //   * The block's own L keys and values (fp32, from the projection) are handled by the whole
 //     workgroup on the vector ALU.
-//   * The prefix cache is walked in chunks of 32 positions, chunk c by wavefront c % 4, and each
+//   * The prefix cache is walked in chunks of 32 positions, chunk c by wavefront c % NW, and each
 //     wavefront runs its own online softmax over its chunks: no workgroup barrier inside the walk.
 //     Both contractions run on the matrix cores on the cache's bf16 values as they are, with the fp32
 //     operand of each (queries, probabilities) as three bf16 terms (x = a + b + c up to 2^-24 |x|):
