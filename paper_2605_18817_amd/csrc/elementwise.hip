@@ -89,13 +89,20 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
     if (i >= M) return;   // (uniform over the workgroup)
     const int C8 = d >> 3;
     float u[NORM_MAX_CHUNKS][8];
+    float4 hv[NORM_MAX_CHUNKS][2];   // the row of h_run, requested with u (one round trip instead of two)
     float ss = 0.f;
 #pragma unroll
     for (int n = 0; n < NORM_MAX_CHUNKS; ++n) {
         const int c8 = threadIdx.x + 256 * n;
 #pragma unroll
         for (int e = 0; e < 8; ++e) u[n][e] = 0.f;
+        hv[n][0] = hv[n][1] = make_float4(0.f, 0.f, 0.f, 0.f);
         if (c8 < C8) {
+            if (carry) {
+                const float4 *hp = reinterpret_cast<const float4 *>(hrun + (size_t)i * d + 8 * c8);
+                hv[n][0] = hp[0];
+                hv[n][1] = hp[1];
+            }
             sum_partials(part, (size_t)M * d, nKs, (size_t)i * d + 8 * c8, u[n]);
             if (resid) {   // transformer body: u = residual stream + last projection
                 const float4 *rp = reinterpret_cast<const float4 *>(resid + (size_t)i * d + 8 * c8);
@@ -126,7 +133,7 @@ __global__ __launch_bounds__(256) void norm_kernel(const float *__restrict__ par
             y[dst] = make_uint4(pack2(yb[0], yb[1]), pack2(yb[2], yb[3]), pack2(yb[4], yb[5]), pack2(yb[6], yb[7]));
             if (carry) {
                 float4 *hp = reinterpret_cast<float4 *>(hrun + (size_t)i * d + 8 * c8);
-                const float4 a = hp[0], b = hp[1];
+                const float4 a = hv[n][0], b = hv[n][1];
                 const float x[8] = {a.x + u[n][0], a.y + u[n][1], a.z + u[n][2], a.w + u[n][3],
                                     b.x + u[n][4], b.y + u[n][5], b.z + u[n][6], b.w + u[n][7]};
                 hp[0] = make_float4(x[0], x[1], x[2], x[3]);
