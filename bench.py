@@ -223,6 +223,8 @@ def bench_tbody(args, np, torch, mi, mrp) -> dict:
     w1, _, g = mi.head_weights(cfg, 0)
     layers_h = [mi.tf_layer(cfg, td, 0, l) for l in range(td.D)]
     plen = mi.prefix_lens(cfg, td)
+    if args.prefix_len is not None:      # every sequence the same committed prefix (attention time by prefix length)
+        plen = np.full_like(plen, min(max(args.prefix_len, 0), td.P_max))
     ctx = mrp.MrpContext(d, V, M, L)
     ctx.tbody_create(td.D, td.n_heads, td.n_kv_heads, td.d_ff, td.P_max, td.rope_theta)
     E_d, Wp_d = bits(E), mrp.pack_weight(bits(W))
@@ -267,7 +269,8 @@ def bench_tbody(args, np, torch, mi, mrp) -> dict:
     return _line(f"MRP draft tokens/sec per step with the transformer head body (D={td.D}) on 1 GPU; % HBM roofline of the LM head",
                  M * K * args.steps / elapsed, "tokens/s", args, elapsed, "bf16",
                  f"config 1 sizes (d={d} V={V} B={B} block={L} K={K}), head body: {td.D} layers, 16/8 heads of 128, d_ff 6144, "
-                 f"prefix lengths uniform in [0, 1024]", roof, cpu)
+                 + ("prefix lengths uniform in [0, 1024]" if args.prefix_len is None
+                    else f"prefix length {int(plen[0])} for every sequence"), roof, cpu)
 
 
 def host_cpu_info():
@@ -439,6 +442,8 @@ def main() -> int:
                          "512-row case that runs on the streaming kernel between the persistent and the tiled one)")
     ap.add_argument("--depth", type=int, default=3,
                     help="--workload tbody: transformer layers per head (the paper's depth sweep uses 1, 2, 3, 4, 8)")
+    ap.add_argument("--prefix-len", type=int, default=None,
+                    help="--workload tbody: give every sequence this prefix length (0..1024) instead of the seeded mix")
     ap.add_argument("--skip-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
