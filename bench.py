@@ -439,7 +439,7 @@ def main() -> int:
                          "configuration 1 in its config1_hbm_regime sub-object)")
     ap.add_argument("--batch", type=int, default=None,
                     help="with --config N: override the number of sequences B (e.g. --config 2 --batch 32 times the "
-                         "512-row case that runs on the streaming kernel between the persistent and the tiled one)")
+                         "512-row case, the last row count on the persistent LM-head kernel before the tile kernel takes over)")
     ap.add_argument("--depth", type=int, default=3,
                     help="--workload tbody: transformer layers per head (the paper's depth sweep uses 1, 2, 3, 4, 8)")
     ap.add_argument("--prefix-len", type=int, default=None,
