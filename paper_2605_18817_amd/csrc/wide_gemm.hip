@@ -99,14 +99,26 @@ __global__ __launch_bounds__(64 * WD_WAVES) __attribute__((amdgpu_waves_per_eu(1
     // all loads at the loop's end.
     const int nch = nkb / WD_CH, last = nch - 1;
     request(0, 0);
+    // Within a trip the requests of the next set are dealt between the MFMAs of the current one (5 requests, then
+    // 8 MFMAs, eight times): a request takes the CU's address unit 16 cycles or more, and a wave that issues its
+    // 40 requests in one burst keeps its SIMD's matrix core idle meanwhile.
+    constexpr int NLD = WD_CH * (WD_NF + NP * WD_RT), NMMA = WD_CH * NP * WD_RT * WD_NF, NGRP = 8;
     for (int c = 0; c + 2 <= nch; c += 2) {
         request(1, c + 1);
-        __builtin_amdgcn_sched_barrier(0);     // (the requests stay ahead of the MFMAs that hide them)
         compute(0);
+#pragma unroll
+        for (int g = 0; g < NGRP; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x020, NLD / NGRP, 0);     // VMEM reads
+            __builtin_amdgcn_sched_group_barrier(0x008, NMMA / NGRP, 0);    // MFMAs
+        }
         __builtin_amdgcn_sched_barrier(0);
         request(0, c + 2 <= last ? c + 2 : last);
-        __builtin_amdgcn_sched_barrier(0);
         compute(1);
+#pragma unroll
+        for (int g = 0; g < NGRP; ++g) {
+            __builtin_amdgcn_sched_group_barrier(0x020, NLD / NGRP, 0);
+            __builtin_amdgcn_sched_group_barrier(0x008, NMMA / NGRP, 0);
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
     if (nch & 1) compute(0);
