@@ -172,12 +172,18 @@ int gemm_partial(mrp_ctx *c, hipStream_t st, const void *Wp, int R, int Kc, cons
     }
     if (small_rows_kernel(M, Kc) && M > 64 && R % 64 == 0 && nplanes <= 2) {
         // 65 .. 512 rows: 64-feature x 128-row tiles with k split over workgroups
-        const int nft = R / 64, nrg = (M + 127) / 128;
-        const int ks = wide_gemm_ksplit(nft * nrg, Kc / 16, c->nCU, out_floats / (size_t)R, M);
+        const int nrg = (M + 127) / 128;
+        // 128-feature tiles halve the activation bytes a CU pulls in per output; they pay once there are enough of
+        // them (measured at 128 rows, d = 2048: the 12288-feature gate/up projection, 96 tiles, 26.5 -> 24 us; with 32
+        // or 16 tiles, the qkv and o / down projections, the step is 2 - 5 % slower)
+        const int nf = (R % 128 == 0 && (R / 128) * nrg >= 96) ? 4 : 2;
+        const int nft = R / (32 * nf);
+        const int ks = wide_gemm_ksplit(nft * nrg, Kc / 16, c->nCU, out_floats / (size_t)R, M, nf);
         if (ks > 0) {
             WideGemmArgs wg;
             wg.Wp = static_cast<const uint4 *>(Wp); wg.X = act; wg.plane = plane_stride; wg.nplanes = nplanes;
             wg.out = out; wg.nIb = c->nIb; wg.M = M; wg.R = R; wg.Kc = Kc; wg.nKs = ks; wg.nft = nft; wg.nrg = nrg;
+            wg.nf = nf;
             *err = launch_wide_gemm(wg, st);
             return *err == hipSuccess ? ks : -1;
         }

@@ -331,9 +331,10 @@ struct WideGemmArgs {
     float *out;                // [nKs][M][R]
     int nIb, M, R, Kc;
     int nKs;                   // k parts (1, 2, 4 or 8)
-    int nft, nrg;              // R / 64 feature tiles, ceil(M / 128) row groups
+    int nft, nrg;              // R / (32 nf) feature tiles, ceil(M / 128) row groups
+    int nf;                    // 32-feature blocks per workgroup: 2 or 4
 };
-int wide_gemm_ksplit(int tiles, int kbs, int nCU, size_t cap_rows, int M);   // 0: not applicable
+int wide_gemm_ksplit(int tiles, int kbs, int nCU, size_t cap_rows, int M, int nf);   // 0: not applicable
 hipError_t launch_wide_gemm(const WideGemmArgs &a, hipStream_t st);
 
 // out [M][R] fp32 = X W^T, k split reduced inside the workgroup (R % 32 == 0, Kc % 128 == 0)
