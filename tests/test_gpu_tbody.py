@@ -134,6 +134,15 @@ def test_160_rows_two_row_groups_of_the_wide_gemm():
     _run(cfg, td, mrp.RevealCfg(tau=0.9), seqs=[0, 4, 9])
 
 
+def test_400_rows_four_row_groups_wide_output():
+    """400 rows (three whole row groups of 128 and one of 16) with a 3072-feature gate/up projection: 96 tiles of 128
+    features, the form of the projection kernel that wide outputs take; sequences from the first, a middle and the
+    last row group are compared."""
+    cfg = mi.straddling(mi.config(0, d=256, V=4096, B=25, L=16, K=1))
+    td = mi.TBodyDims(D=1, n_heads=2, n_kv_heads=1, head_dim=128, d_ff=1536, P_max=40)
+    _run(cfg, td, mrp.RevealCfg(tau=0.9), seqs=[0, 11, 24])
+
+
 def test_long_prefix_shared_by_four_workgroups():
     """Two (kv head, sequence) pairs with a 1024-position cache: four workgroups per pair; sequence 0 has no
     prefix (its three extra workgroups write empty partials), sequence 1 a full one."""
